@@ -1,0 +1,21 @@
+import os
+import sys
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+
+def pytest_configure(config):
+    config.addinivalue_line("markers", "gpu: needs a real MI355X (run with -m gpu)")
+
+
+@pytest.fixture(scope="session", autouse=True)
+def _oracle_built():
+    # the C oracle is compiled by __graft_entry__.build(); build it here only if it is absent
+    from oracle import build as ob
+    if not os.path.exists(ob.LIB):
+        ob.build()
+    yield
