@@ -1,0 +1,226 @@
+// KV append and the row-streaming paged prefix attention kernel.
+//
+// What is computed (paper sections 2.1 and 4.2: a query reuses the KV of its matched
+// prefix and attends over it together with the KV of its own new tokens; section 4.3: new
+// KV stays in the pool): for new token j of sequence i (position p = prefix_len + j) and
+// query head h, softmax over positions 0..p of sm_scale * q.K, times V, with K and V read
+// through the sequence's block table.
+//
+// Block layout used here: K of (kv head g, slot s, channel c) at ((g*16 + s)*D + c); V of
+// the same at n_kv*16*D + ((g*D + c)*16 + s).  V is stored transposed so that the 16
+// positions of one channel are one contiguous run: a lane that owns a channel reads them
+// with one or two 16-byte loads and accumulates P.V without any cross-lane traffic.
+#include <hip/hip_runtime.h>
+
+#include "flp_internal.h"
+#include "flp_types.h"
+
+namespace {
+
+constexpr int BT = 16;   // token positions per block
+
+// ------------------------------------------------------------------------------- append
+// One workgroup per (sequence, block) unit: copies the K rows of the unit's slots and
+// writes the V columns transposed, a full 16-slot run per (head, channel) when the unit
+// covers the whole block.
+template <typename S, int D>
+__global__ __launch_bounds__(256) void kv_append_kernel(FlpAttnArgs a, const FlpAppendUnit* __restrict__ units) {
+  const FlpAppendUnit u = units[blockIdx.x];
+  const int64_t blk = a.tables[(int64_t)u.seq * a.max_blocks + u.blk_idx];
+  S* __restrict__ base = reinterpret_cast<S*>(a.pool) + blk * a.block_elems;
+  const S* __restrict__ kn = reinterpret_cast<const S*>(a.k_new);
+  const S* __restrict__ vn = reinterpret_cast<const S*>(a.v_new);
+  const int row = a.n_kv * D;          // elements per token in k_new / v_new
+  const int ns = u.s1 - u.s0;
+  // K: rows of D contiguous elements
+  for (int idx = threadIdx.x; idx < ns * row; idx += 256) {
+    int s = idx / row, e = idx - s * row;
+    int g = e / D, c = e - g * D;
+    base[((int64_t)g * BT + (u.s0 + s)) * D + c] = kn[(int64_t)(u.t_first + s) * row + e];
+  }
+  // V: element e = (g, c) of each slot goes to ((g*D + c)*16 + slot)
+  S* __restrict__ vbase = base + (int64_t)a.n_kv * BT * D;
+  for (int e = threadIdx.x; e < row; e += 256) {
+    S* dst = vbase + (int64_t)e * BT;   // (g*D + c) == e
+    if (ns == BT) {
+      S vals[BT];
+#pragma unroll
+      for (int s = 0; s < BT; ++s) vals[s] = vn[(int64_t)(u.t_first + s) * row + e];
+      constexpr int NV = BT * (int)sizeof(S) / 16;
+      u32x4 packed[NV];
+      __builtin_memcpy(packed, vals, sizeof(vals));
+#pragma unroll
+      for (int v = 0; v < NV; ++v) reinterpret_cast<u32x4*>(dst)[v] = packed[v];
+    } else {
+      for (int s = 0; s < ns; ++s) dst[u.s0 + s] = vn[(int64_t)(u.t_first + s) * row + e];
+    }
+  }
+}
+
+// --------------------------------------------------------------------- row-streaming attention
+// One wave per (token, query head) row; a workgroup is four heads of one unit's tokens.
+// Per block of 16 positions: K rows are read 16 bytes per lane (LPK lanes cover one key),
+// scores are reduced inside each LPK-lane group, the online-softmax statistics are kept
+// wave-uniform, and each lane accumulates its D/64 channels from the transposed V rows.
+// HBM-bound for decode (one row per sequence and head); also the generic path for fp32.
+template <typename S, int D>
+struct RowCfg {
+  static constexpr int EPL = 16 / (int)sizeof(typename S::storage);   // elements per 16-byte load
+  static constexpr int LPK = D / EPL;                                 // lanes per key row
+  static constexpr int KPL = 64 / LPK;                                // keys per wave-wide load
+  static constexpr int NLD = BT / KPL;                                // loads per 16-key block
+  static constexpr int CPL = D / 64;                                  // channels per lane
+  static constexpr int VLD = BT * (int)sizeof(typename S::storage) / 16;   // 16-byte loads per V row
+};
+
+template <typename S, int D>
+__global__ __launch_bounds__(256) void attn_rows_kernel(FlpAttnArgs a, const FlpAttnUnit* __restrict__ units) {
+  typedef typename S::storage ST;
+  typedef RowCfg<S, D> C;
+  const FlpAttnUnit u = units[blockIdx.x];
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int h = blockIdx.y * 4 + wave;
+  if (h >= a.n_h) return;
+  const int g = h / (a.n_h / a.n_kv);
+  const int P = a.prefix_len[u.seq];
+  const int t0 = a.cu_new[u.seq];
+  const int32_t* __restrict__ table = a.tables + (int64_t)u.seq * a.max_blocks;
+  const ST* __restrict__ pool = reinterpret_cast<const ST*>(a.pool);
+  const int ck = lane % C::LPK;     // which 16-byte chunk of a key row this lane reads
+  const int kg = lane / C::LPK;     // which key of a wave-wide load this lane works on
+  const int64_t v_region = (int64_t)a.n_kv * BT * D;
+
+  for (int jj = 0; jj < u.n_tok; ++jj) {
+    const int j = u.j0 + jj;
+    const int t = t0 + j;
+    const int ctx = P + j + 1;      // positions 0..P+j are visible
+    float qf[C::EPL];
+    {
+      const ST* qp = reinterpret_cast<const ST*>(a.q) + ((int64_t)t * a.n_h + h) * D + ck * C::EPL;
+      u32x4 raw = *reinterpret_cast<const u32x4*>(qp);
+      ST tmp[C::EPL];
+      __builtin_memcpy(tmp, &raw, 16);
+#pragma unroll
+      for (int e = 0; e < C::EPL; ++e) qf[e] = S::to_float(tmp[e]) * a.scale_log2e;
+    }
+    float m = -INFINITY, l = 0.f;
+    float acc[C::CPL];
+#pragma unroll
+    for (int c = 0; c < C::CPL; ++c) acc[c] = 0.f;
+
+    const int nblk = (ctx + BT - 1) / BT;
+    for (int b = 0; b < nblk; ++b) {
+      const ST* __restrict__ base = pool + (int64_t)table[b] * a.block_elems;
+      // ---- scores of the block's 16 keys
+      float s[C::NLD];
+#pragma unroll
+      for (int i = 0; i < C::NLD; ++i) {
+        const int key = i * C::KPL + kg;
+        u32x4 raw = *reinterpret_cast<const u32x4*>(base + ((int64_t)g * BT + key) * D + ck * C::EPL);
+        ST tmp[C::EPL];
+        __builtin_memcpy(tmp, &raw, 16);
+        float d = 0.f;
+#pragma unroll
+        for (int e = 0; e < C::EPL; ++e) d = fmaf(qf[e], S::to_float(tmp[e]), d);
+#pragma unroll
+        for (int off = 1; off < C::LPK; off <<= 1) d += __shfl_xor(d, off);
+        s[i] = (b * BT + key < ctx) ? d : -INFINITY;
+      }
+      float bm = s[0];
+#pragma unroll
+      for (int i = 1; i < C::NLD; ++i) bm = fmaxf(bm, s[i]);
+#pragma unroll
+      for (int off = C::LPK; off < 64; off <<= 1) bm = fmaxf(bm, __shfl_xor(bm, off));
+      const float m_new = fmaxf(m, bm);          // finite: the block holds at least one visible key
+      const float alpha = exp2f(m - m_new);      // 0 on the first block (m = -inf)
+      float psum = 0.f;
+#pragma unroll
+      for (int i = 0; i < C::NLD; ++i) {
+        s[i] = exp2f(s[i] - m_new);              // masked keys: exp2(-inf) = 0
+        psum += s[i];
+      }
+#pragma unroll
+      for (int off = C::LPK; off < 64; off <<= 1) psum += __shfl_xor(psum, off);
+      l = l * alpha + psum;
+      m = m_new;
+      // ---- weights of the 16 keys, wave-uniform
+      float w[BT];
+#pragma unroll
+      for (int k = 0; k < BT; ++k)
+        w[k] = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(s[k / C::KPL]), (k % C::KPL) * C::LPK));
+      // ---- P.V: this lane's channels, 16 positions each
+#pragma unroll
+      for (int c = 0; c < C::CPL; ++c) {
+        const ST* vp = base + v_region + ((int64_t)g * D + (lane + 64 * c)) * BT;
+        ST vv[BT];
+        u32x4 raw[C::VLD];
+#pragma unroll
+        for (int v = 0; v < C::VLD; ++v) raw[v] = reinterpret_cast<const u32x4*>(vp)[v];
+        __builtin_memcpy(vv, raw, sizeof(vv));
+        float part = 0.f;
+#pragma unroll
+        for (int k = 0; k < BT; ++k) {
+          // slots past the sequence's length hold arbitrary bits: select, never multiply
+          float x = (b * BT + k < ctx) ? S::to_float(vv[k]) : 0.f;
+          part = fmaf(w[k], x, part);
+        }
+        acc[c] = acc[c] * alpha + part;
+      }
+    }
+    const float inv = 1.f / l;
+    ST* op = reinterpret_cast<ST*>(a.out) + ((int64_t)t * a.n_h + h) * D;
+#pragma unroll
+    for (int c = 0; c < C::CPL; ++c) op[lane + 64 * c] = S::from_float(acc[c] * inv);
+  }
+}
+
+}  // namespace
+
+#define FLP_DISPATCH(KERNEL, dtype, head_dim, grid, block, stream, ...)                                      \
+  do {                                                                                                       \
+    if (dtype == FLP_F32 && head_dim == 64)                                                                  \
+      hipLaunchKernelGGL((KERNEL<F32, 64>), grid, block, 0, stream, __VA_ARGS__);                            \
+    else if (dtype == FLP_F32 && head_dim == 128)                                                            \
+      hipLaunchKernelGGL((KERNEL<F32, 128>), grid, block, 0, stream, __VA_ARGS__);                           \
+    else if (dtype == FLP_F16 && head_dim == 64)                                                             \
+      hipLaunchKernelGGL((KERNEL<F16, 64>), grid, block, 0, stream, __VA_ARGS__);                            \
+    else if (dtype == FLP_F16 && head_dim == 128)                                                            \
+      hipLaunchKernelGGL((KERNEL<F16, 128>), grid, block, 0, stream, __VA_ARGS__);                           \
+    else if (dtype == FLP_BF16 && head_dim == 64)                                                            \
+      hipLaunchKernelGGL((KERNEL<BF16, 64>), grid, block, 0, stream, __VA_ARGS__);                           \
+    else if (dtype == FLP_BF16 && head_dim == 128)                                                           \
+      hipLaunchKernelGGL((KERNEL<BF16, 128>), grid, block, 0, stream, __VA_ARGS__);                          \
+    else {                                                                                                   \
+      flp_set_error("attention: dtype %d / head_dim %d not supported", dtype, head_dim);                     \
+      return FLP_ENOTSUP;                                                                                    \
+    }                                                                                                        \
+  } while (0)
+
+flp_status flp_launch_kv_append(int dtype, int head_dim, const FlpAttnArgs& a, const FlpAppendUnit* units_dev,
+                                int32_t n_units, hipStream_t stream) {
+  if (n_units <= 0) return FLP_OK;
+  // the append kernel only moves storage words: fp16 and bf16 share the 16-bit instance
+  if (dtype == FLP_F32 && head_dim == 64)
+    hipLaunchKernelGGL((kv_append_kernel<float, 64>), dim3(n_units), dim3(256), 0, stream, a, units_dev);
+  else if (dtype == FLP_F32 && head_dim == 128)
+    hipLaunchKernelGGL((kv_append_kernel<float, 128>), dim3(n_units), dim3(256), 0, stream, a, units_dev);
+  else if (dtype != FLP_F32 && head_dim == 64)
+    hipLaunchKernelGGL((kv_append_kernel<uint16_t, 64>), dim3(n_units), dim3(256), 0, stream, a, units_dev);
+  else if (dtype != FLP_F32 && head_dim == 128)
+    hipLaunchKernelGGL((kv_append_kernel<uint16_t, 128>), dim3(n_units), dim3(256), 0, stream, a, units_dev);
+  else {
+    flp_set_error("kv_append: head_dim %d not supported", head_dim);
+    return FLP_ENOTSUP;
+  }
+  FLP_TRY_HIP(hipGetLastError());
+  return FLP_OK;
+}
+
+flp_status flp_launch_attn_rows(int dtype, int head_dim, const FlpAttnArgs& a, const FlpAttnUnit* units_dev,
+                                int32_t n_units, hipStream_t stream) {
+  if (n_units <= 0) return FLP_OK;
+  dim3 grid((unsigned)n_units, (unsigned)((a.n_h + 3) / 4));
+  FLP_DISPATCH(attn_rows_kernel, dtype, head_dim, grid, dim3(256), stream, a, units_dev);
+  FLP_TRY_HIP(hipGetLastError());
+  return FLP_OK;
+}

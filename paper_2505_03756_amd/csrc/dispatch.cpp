@@ -1,0 +1,267 @@
+// Host-side dispatch of the compute entry points: argument checks, the work lists built
+// from the host-resident sequence lengths, and the launches.
+#include <algorithm>
+#include <cmath>
+#include <cstring>
+#include <numeric>
+
+#include "flp_internal.h"
+
+namespace {
+
+bool aligned16(const void* p) { return ((uintptr_t)p & 15) == 0; }
+
+flp_status check_attn_batch(const flp_pool* p, const flp_attn_batch* b, bool need_qo, bool need_kv, const char* who) {
+  if (!p || !b) {
+    flp_set_error("%s: null pool or batch", who);
+    return FLP_EINVAL;
+  }
+  if (b->n_seqs < 0 || b->max_blocks_per_seq < 0 || (b->n_seqs > 0 && (!b->cu_new || !b->prefix_len || !b->block_tables))) {
+    flp_set_error("%s: bad sequence arrays", who);
+    return FLP_EINVAL;
+  }
+  if (p->cfg.block_tokens != 16 || (p->cfg.head_dim != 64 && p->cfg.head_dim != 128)) {
+    flp_set_error("%s: kernels support block_tokens 16 and head_dim 64/128 (pool has %d / %d)", who,
+                  p->cfg.block_tokens, p->cfg.head_dim);
+    return FLP_ENOTSUP;
+  }
+  if (need_qo) {
+    if (b->n_q_heads <= 0 || b->n_q_heads % p->cfg.n_kv_heads) {
+      flp_set_error("%s: n_q_heads %d is not a multiple of n_kv_heads %d", who, b->n_q_heads, p->cfg.n_kv_heads);
+      return FLP_EINVAL;
+    }
+  }
+  if (b->n_seqs > 0 && b->cu_new[0] != 0) {
+    flp_set_error("%s: cu_new[0] must be 0", who);
+    return FLP_EINVAL;
+  }
+  const int64_t cap = (int64_t)b->max_blocks_per_seq * p->cfg.block_tokens;
+  for (int32_t i = 0; i < b->n_seqs; ++i) {
+    int64_t n = (int64_t)b->cu_new[i + 1] - b->cu_new[i];
+    if (n < 0 || b->prefix_len[i] < 0) {
+      flp_set_error("%s: sequence %d has negative length", who, i);
+      return FLP_EINVAL;
+    }
+    if (b->prefix_len[i] + n > cap) {
+      flp_set_error("%s: sequence %d needs %lld positions, its block table covers %lld", who, i,
+                    (long long)(b->prefix_len[i] + n), (long long)cap);
+      return FLP_ERANGE;
+    }
+  }
+  const int32_t T = b->n_seqs > 0 ? b->cu_new[b->n_seqs] : 0;
+  if (T > 0) {
+    if (need_qo && (!b->q || !b->out || !aligned16(b->q) || !aligned16(b->out))) {
+      flp_set_error("%s: q/out must be non-null and 16-byte aligned", who);
+      return FLP_EINVAL;
+    }
+    if (need_kv && (!b->k_new || !b->v_new || !aligned16(b->k_new) || !aligned16(b->v_new))) {
+      flp_set_error("%s: k_new/v_new must be non-null and 16-byte aligned", who);
+      return FLP_EINVAL;
+    }
+  }
+  return FLP_OK;
+}
+
+// device copies of cu_new / prefix_len plus a unit list, in one staging slot
+struct StagedSeqs {
+  FlpStageSlot* slot = nullptr;
+  const int32_t* cu_new = nullptr;
+  const int32_t* prefix_len = nullptr;
+  const void* units = nullptr;
+};
+
+template <typename Unit>
+flp_status stage_seqs(flp_pool* p, const flp_attn_batch* b, const std::vector<Unit>& units, hipStream_t stream,
+                      StagedSeqs* out) {
+  const size_t S = (size_t)b->n_seqs;
+  const size_t off_pl = (S + 1) * 4, off_units = ((off_pl + S * 4 + 31) / 32) * 32;
+  const size_t bytes = off_units + units.size() * sizeof(Unit);
+  FLP_TRY(flp_stage_acquire(p, bytes, &out->slot));
+  uint8_t* h = (uint8_t*)out->slot->host;
+  memcpy(h, b->cu_new, (S + 1) * 4);
+  memcpy(h + off_pl, b->prefix_len, S * 4);
+  if (!units.empty()) memcpy(h + off_units, units.data(), units.size() * sizeof(Unit));
+  FLP_TRY(flp_stage_upload(out->slot, bytes, stream));
+  const uint8_t* d = (const uint8_t*)out->slot->dev;
+  out->cu_new = (const int32_t*)d;
+  out->prefix_len = (const int32_t*)(d + off_pl);
+  out->units = d + off_units;
+  return FLP_OK;
+}
+
+FlpAttnArgs make_args(const flp_pool* p, const flp_attn_batch* b, const StagedSeqs& st) {
+  FlpAttnArgs a{};
+  a.pool = p->dev_base;
+  a.block_elems = p->block_elems;
+  a.tables = b->block_tables;
+  a.max_blocks = b->max_blocks_per_seq;
+  a.n_h = b->n_q_heads;
+  a.n_kv = p->cfg.n_kv_heads;
+  a.q = b->q;
+  a.out = b->out;
+  a.k_new = b->k_new;
+  a.v_new = b->v_new;
+  a.cu_new = st.cu_new;
+  a.prefix_len = st.prefix_len;
+  float sc = b->sm_scale > 0.f ? b->sm_scale : 1.0f / std::sqrt((float)p->cfg.head_dim);
+  a.scale_log2e = sc * 1.4426950408889634f;
+  return a;
+}
+
+flp_status append_locked(flp_pool* p, const flp_attn_batch* b, hipStream_t stream) {
+  const int bt = p->cfg.block_tokens;
+  std::vector<FlpAppendUnit> units;
+  for (int32_t i = 0; i < b->n_seqs; ++i) {
+    const int32_t P = b->prefix_len[i], n = b->cu_new[i + 1] - b->cu_new[i];
+    int32_t pos = P;
+    while (pos < P + n) {
+      FlpAppendUnit u{};
+      u.seq = i;
+      u.blk_idx = pos / bt;
+      u.s0 = pos % bt;
+      u.s1 = std::min<int32_t>(bt, u.s0 + (P + n - pos));
+      u.t_first = b->cu_new[i] + (pos - P);
+      units.push_back(u);
+      pos += u.s1 - u.s0;
+    }
+  }
+  if (units.empty()) return FLP_OK;
+  StagedSeqs st;
+  FLP_TRY(stage_seqs(p, b, units, stream, &st));
+  FlpAttnArgs a = make_args(p, b, st);
+  flp_status s1 = flp_launch_kv_append(p->cfg.dtype, p->cfg.head_dim, a, (const FlpAppendUnit*)st.units,
+                                       (int32_t)units.size(), stream);
+  flp_status s2 = flp_stage_release(st.slot, stream);
+  return s1 != FLP_OK ? s1 : s2;
+}
+
+}  // namespace
+
+extern "C" flp_status flp_kv_append(flp_pool* p, const flp_attn_batch* b, void* hip_stream) {
+  FLP_TRY(check_attn_batch(p, b, false, true, "flp_kv_append"));
+  std::lock_guard<std::mutex> lk(p->mu);
+  return append_locked(p, b, (hipStream_t)hip_stream);
+}
+
+extern "C" flp_status flp_paged_prefix_attention(flp_pool* p, const flp_attn_batch* b, void* hip_stream) {
+  const bool with_append = b && (b->k_new || b->v_new);
+  FLP_TRY(check_attn_batch(p, b, true, with_append, "flp_paged_prefix_attention"));
+  std::lock_guard<std::mutex> lk(p->mu);
+  hipStream_t stream = (hipStream_t)hip_stream;
+  if (with_append) FLP_TRY(append_locked(p, b, stream));
+
+  // work units: runs of up to 4 new tokens of one sequence, heaviest first so that the
+  // long contexts start early and the short ones fill the tail
+  std::vector<FlpAttnUnit> units;
+  std::vector<int64_t> cost;
+  constexpr int kTokPerUnit = 4;
+  for (int32_t i = 0; i < b->n_seqs; ++i) {
+    const int32_t n = b->cu_new[i + 1] - b->cu_new[i];
+    for (int32_t j0 = 0; j0 < n; j0 += kTokPerUnit) {
+      FlpAttnUnit u{i, j0, std::min(kTokPerUnit, n - j0), 0};
+      units.push_back(u);
+      cost.push_back((int64_t)u.n_tok * (b->prefix_len[i] + j0 + u.n_tok));
+    }
+  }
+  if (units.empty()) return FLP_OK;
+  std::vector<int32_t> order(units.size());
+  std::iota(order.begin(), order.end(), 0);
+  std::stable_sort(order.begin(), order.end(), [&](int32_t x, int32_t y) { return cost[x] > cost[y]; });
+  std::vector<FlpAttnUnit> sorted(units.size());
+  for (size_t k = 0; k < order.size(); ++k) sorted[k] = units[order[k]];
+
+  StagedSeqs st;
+  FLP_TRY(stage_seqs(p, b, sorted, stream, &st));
+  FlpAttnArgs a = make_args(p, b, st);
+  flp_status s1 = flp_launch_attn_rows(p->cfg.dtype, p->cfg.head_dim, a, (const FlpAttnUnit*)st.units,
+                                       (int32_t)sorted.size(), stream);
+  flp_status s2 = flp_stage_release(st.slot, stream);
+  return s1 != FLP_OK ? s1 : s2;
+}
+
+// ------------------------------------------------------------------------------- LoRA
+extern "C" flp_status flp_lora_segment(flp_pool* p, int32_t n_tokens, const int32_t* token_adapter,
+                                       int32_t n_adapters, int32_t* n_seg, int32_t* seg_adapter, int32_t* seg_start,
+                                       int32_t* perm, void* hip_stream) {
+  if (!p || n_tokens < 0 || n_adapters < 0 || !n_seg || !seg_adapter || !seg_start || (n_tokens > 0 && (!token_adapter || !perm))) {
+    flp_set_error("flp_lora_segment: invalid argument");
+    return FLP_EINVAL;
+  }
+  if (n_adapters > 2048) {
+    flp_set_error("flp_lora_segment: %d adapters, at most 2048 supported", n_adapters);
+    return FLP_ERANGE;
+  }
+  return flp_launch_lora_segment(n_tokens, token_adapter, n_adapters, n_seg, seg_adapter, seg_start, perm,
+                                 (hipStream_t)hip_stream);
+}
+
+extern "C" flp_status flp_lora_apply_paged(flp_pool* p, const flp_lora_batch* b, void* hip_stream) {
+  if (!p || !b) {
+    flp_set_error("flp_lora_apply_paged: null pool or batch");
+    return FLP_EINVAL;
+  }
+  if (b->n_tokens < 0 || b->n_proj < 1 || b->n_proj > FLP_MAX_PROJ || b->n_adapters < 0 || b->d_in <= 0 ||
+      b->ld_x < b->d_in) {
+    flp_set_error("flp_lora_apply_paged: bad sizes (n_tokens=%d n_proj=%d n_adapters=%d d_in=%d ld_x=%lld)",
+                  b->n_tokens, b->n_proj, b->n_adapters, b->d_in, (long long)b->ld_x);
+    return FLP_EINVAL;
+  }
+  if (b->n_tokens == 0) return FLP_OK;
+  if (b->max_rank < 1 || b->max_rank > 64) {
+    flp_set_error("flp_lora_apply_paged: max_rank %d outside 1..64", b->max_rank);
+    return FLP_ERANGE;
+  }
+  if (b->n_adapters > 2048) {
+    flp_set_error("flp_lora_apply_paged: %d adapters, at most 2048 supported", b->n_adapters);
+    return FLP_ERANGE;
+  }
+  const int epl = 16 / p->elem_bytes;
+  if (!b->x || !b->token_adapter || !b->rank || !b->scale || !b->block_tables || !aligned16(b->x) ||
+      b->d_in % epl || b->ld_x % epl || b->d_in > p->block_elems) {
+    flp_set_error("flp_lora_apply_paged: x/metadata null or misaligned, or d_in %d not a multiple of %d / larger than a block",
+                  b->d_in, epl);
+    return FLP_EINVAL;
+  }
+  for (int q = 0; q < b->n_proj; ++q) {
+    const flp_lora_proj& pr = b->proj[q];
+    if (pr.d_out <= 0 || pr.ld_y < pr.d_out || pr.d_out % epl || pr.ld_y % epl || pr.d_out > p->block_elems || !pr.y ||
+        !aligned16(pr.y) || !pr.a_tab_off || !pr.a_row_base || !pr.b_tab_off || !pr.b_row_base) {
+      flp_set_error("flp_lora_apply_paged: projection %d has bad sizes or null/misaligned pointers", q);
+      return FLP_EINVAL;
+    }
+    if (pr.w_base) {
+      flp_set_error("flp_lora_apply_paged: w_base is not supported yet; put x.W_base into y and pass NULL");
+      return FLP_ENOTSUP;
+    }
+  }
+  std::lock_guard<std::mutex> lk(p->mu);
+  hipStream_t stream = (hipStream_t)hip_stream;
+  const size_t T = (size_t)b->n_tokens;
+  const size_t v_bytes = ((T * b->n_proj * b->max_rank * 4) + 255) & ~(size_t)255;
+  const size_t seg_bytes = ((size_t)(2 * b->n_adapters + 2 + 1) * 4 + 255) & ~(size_t)255;
+  const size_t perm_bytes = (T * 4 + 255) & ~(size_t)255;
+  void* ws = nullptr;
+  FLP_TRY(flp_workspace(p, v_bytes + seg_bytes + perm_bytes, &ws));
+  FlpLoraArgs a{};
+  a.pool = p->dev_base;
+  a.block_elems = p->block_elems;
+  a.T = b->n_tokens;
+  a.d_in = b->d_in;
+  a.n_adapters = b->n_adapters;
+  a.max_rank = b->max_rank;
+  a.n_proj = b->n_proj;
+  a.ld_x = b->ld_x;
+  a.x = b->x;
+  a.token_adapter = b->token_adapter;
+  a.rank = b->rank;
+  a.scale = b->scale;
+  a.tables = b->block_tables;
+  for (int q = 0; q < b->n_proj; ++q) a.proj[q] = b->proj[q];
+  uint8_t* w = (uint8_t*)ws;
+  a.v = (float*)w;
+  a.n_seg = (int32_t*)(w + v_bytes);
+  a.seg_adapter = a.n_seg + 1;
+  a.seg_start = a.seg_adapter + b->n_adapters;
+  a.perm = (int32_t*)(w + v_bytes + seg_bytes);
+  return flp_launch_lora_simple(p->cfg.dtype, a, stream);
+}

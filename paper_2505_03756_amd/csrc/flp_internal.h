@@ -1,0 +1,129 @@
+// Internal declarations shared by the host logic (pool.cpp, dispatch.cpp) and the
+// kernel translation units.  Not part of the ABI.
+#pragma once
+
+#include <hip/hip_runtime_api.h>
+
+#include <cstdint>
+#include <mutex>
+#include <vector>
+
+#include "flpool.h"
+
+void flp_set_error(const char* fmt, ...) __attribute__((format(printf, 1, 2)));
+
+#define FLP_TRY_HIP(expr)                                                                        \
+  do {                                                                                           \
+    hipError_t e_ = (expr);                                                                      \
+    if (e_ != hipSuccess) {                                                                      \
+      flp_set_error("%s failed: %s (%s:%d)", #expr, hipGetErrorString(e_), __FILE__, __LINE__);  \
+      return FLP_EHIP;                                                                           \
+    }                                                                                            \
+  } while (0)
+
+#define FLP_TRY(expr)            \
+  do {                           \
+    flp_status s_ = (expr);      \
+    if (s_ != FLP_OK) return s_; \
+  } while (0)
+
+// LIFO free list of one tier.
+struct FlpFreeList {
+  int64_t n = 0;
+  std::vector<int32_t> stack;     // stack.back() is handed out next
+  std::vector<uint8_t> is_free;
+  std::vector<uint32_t> stamp;    // scratch for duplicate detection
+  uint32_t gen = 0;
+};
+
+// One slot of the ring that carries small host arrays (id lists, work lists) to the
+// device: pinned host buffer + device mirror + the event that marks the slot's last use.
+struct FlpStageSlot {
+  void* host = nullptr;
+  void* dev = nullptr;
+  size_t cap = 0;
+  hipEvent_t ev = nullptr;
+  bool in_flight = false;
+};
+
+constexpr int kStageSlots = 8;
+
+struct flp_pool {
+  flp_pool_config cfg{};
+  int elem_bytes = 0;
+  int64_t block_elems = 0;
+  int64_t block_bytes = 0;
+  int device = 0;
+  uint8_t* dev_base = nullptr;
+  uint8_t* host_base = nullptr;
+  bool own_dev = false, own_host = false;
+  FlpFreeList tier[2];
+  FlpStageSlot stage[kStageSlots];
+  int stage_next = 0;
+  void* work = nullptr;           // device workspace (LoRA intermediates), grown on demand
+  size_t work_cap = 0;
+  std::mutex mu;
+};
+
+// Staging: acquire a slot with room for `bytes` (waits for the slot's previous use),
+// fill slot->host, then flp_stage_upload() copies to slot->dev on the stream; after the
+// consuming kernels are enqueued call flp_stage_release().
+flp_status flp_stage_acquire(flp_pool* pool, size_t bytes, FlpStageSlot** slot);
+flp_status flp_stage_upload(FlpStageSlot* slot, size_t bytes, hipStream_t stream);
+flp_status flp_stage_release(FlpStageSlot* slot, hipStream_t stream);
+flp_status flp_workspace(flp_pool* pool, size_t bytes, void** out);
+
+// ---- kernel launchers (defined in the .hip files) ---------------------------------------
+flp_status flp_launch_copy_blocks(const uint8_t* src_base, uint8_t* dst_base, const int32_t* src_ids_dev,
+                                  const int32_t* dst_ids_dev, int32_t n, int64_t block_bytes,
+                                  hipStream_t stream);
+
+struct FlpAppendUnit {   // the slots [s0, s1) of block `blk_idx` of sequence `seq`
+  int32_t seq, blk_idx, s0, s1, t_first, pad0, pad1, pad2;
+};
+struct FlpAttnUnit {     // new tokens [j0, j0+n_tok) of sequence `seq`
+  int32_t seq, j0, n_tok, pad;
+};
+
+struct FlpAttnArgs {
+  uint8_t* pool;
+  int64_t block_elems;
+  const int32_t* tables;
+  int32_t max_blocks;
+  int32_t n_h, n_kv;
+  const void* q;
+  void* out;
+  const void* k_new;
+  const void* v_new;
+  const int32_t* cu_new;       // device copies
+  const int32_t* prefix_len;
+  float scale_log2e;
+};
+
+flp_status flp_launch_kv_append(int dtype, int head_dim, const FlpAttnArgs& a, const FlpAppendUnit* units_dev,
+                                int32_t n_units, hipStream_t stream);
+flp_status flp_launch_attn_rows(int dtype, int head_dim, const FlpAttnArgs& a, const FlpAttnUnit* units_dev,
+                                int32_t n_units, hipStream_t stream);
+
+struct FlpLoraArgs {
+  const uint8_t* pool;
+  int64_t block_elems;
+  int32_t T, d_in, n_adapters, max_rank, n_proj;
+  int64_t ld_x;
+  const void* x;
+  const int32_t* token_adapter;
+  const int32_t* rank;
+  const float* scale;
+  const int32_t* tables;
+  flp_lora_proj proj[FLP_MAX_PROJ];
+  // workspace
+  float* v;                    // [T, n_proj, max_rank] fp32
+  int32_t* n_seg;
+  int32_t* seg_adapter;
+  int32_t* seg_start;
+  int32_t* perm;
+};
+
+flp_status flp_launch_lora_segment(int32_t T, const int32_t* token_adapter, int32_t n_adapters, int32_t* n_seg,
+                                   int32_t* seg_adapter, int32_t* seg_start, int32_t* perm, hipStream_t stream);
+flp_status flp_launch_lora_simple(int dtype, const FlpLoraArgs& a, hipStream_t stream);

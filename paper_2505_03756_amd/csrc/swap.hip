@@ -1,0 +1,71 @@
+// Block gather/scatter copy behind swap-in and swap-out (paper sections 3.2, 4.3, 5.3:
+// the swapper's decisions are executed as moves of whole pool blocks between the host
+// tier and the device tier).  One launch moves the whole list: workgroups walk a
+// (block, chunk) grid and copy 16 bytes per lane with several loads in flight, reading or
+// writing the pinned host tier directly over the host link, so the cost per block is the
+// transfer itself rather than one copy-engine submission per block.
+#include <hip/hip_runtime.h>
+
+#include "flp_internal.h"
+
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int kUnroll = 4;
+
+template <typename V>
+__global__ __launch_bounds__(kThreads) void copy_blocks_kernel(const uint8_t* __restrict__ src_base,
+                                                               uint8_t* __restrict__ dst_base,
+                                                               const int32_t* __restrict__ src_ids,
+                                                               const int32_t* __restrict__ dst_ids,
+                                                               int64_t block_bytes, int32_t chunks_per_block,
+                                                               int64_t vec_per_chunk) {
+  const int32_t blk = blockIdx.x / chunks_per_block;
+  const int32_t chunk = blockIdx.x - blk * chunks_per_block;
+  const V* __restrict__ s = reinterpret_cast<const V*>(src_base + (int64_t)src_ids[blk] * block_bytes);
+  V* __restrict__ d = reinterpret_cast<V*>(dst_base + (int64_t)dst_ids[blk] * block_bytes);
+  const int64_t nvec = block_bytes / (int64_t)sizeof(V);
+  const int64_t lo = (int64_t)chunk * vec_per_chunk;
+  const int64_t hi = lo + vec_per_chunk < nvec ? lo + vec_per_chunk : nvec;
+  for (int64_t i = lo + threadIdx.x; i < hi; i += kThreads * kUnroll) {
+    V r[kUnroll];
+#pragma unroll
+    for (int u = 0; u < kUnroll; ++u) {
+      int64_t j = i + (int64_t)u * kThreads;
+      if (j < hi) r[u] = __builtin_nontemporal_load(s + j);
+    }
+#pragma unroll
+    for (int u = 0; u < kUnroll; ++u) {
+      int64_t j = i + (int64_t)u * kThreads;
+      if (j < hi) __builtin_nontemporal_store(r[u], d + j);
+    }
+  }
+}
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+}  // namespace
+
+flp_status flp_launch_copy_blocks(const uint8_t* src_base, uint8_t* dst_base, const int32_t* src_ids_dev,
+                                  const int32_t* dst_ids_dev, int32_t n, int64_t block_bytes, hipStream_t stream) {
+  if (n <= 0) return FLP_OK;
+  const int64_t chunk_bytes = 16384;
+  int64_t chunks = (block_bytes + chunk_bytes - 1) / chunk_bytes;
+  if ((int64_t)n * chunks > 0x7fffffffLL) {
+    flp_set_error("swap: list of %d blocks is too long for one launch", n);
+    return FLP_ERANGE;
+  }
+  dim3 grid((unsigned)((int64_t)n * chunks));
+  if (block_bytes % 16 == 0) {
+    hipLaunchKernelGGL(copy_blocks_kernel<u32x4>, grid, dim3(kThreads), 0, stream, src_base, dst_base, src_ids_dev,
+                       dst_ids_dev, block_bytes, (int32_t)chunks, chunk_bytes / 16);
+  } else if (block_bytes % 4 == 0) {
+    hipLaunchKernelGGL(copy_blocks_kernel<uint32_t>, grid, dim3(kThreads), 0, stream, src_base, dst_base,
+                       src_ids_dev, dst_ids_dev, block_bytes, (int32_t)chunks, chunk_bytes / 4);
+  } else {
+    hipLaunchKernelGGL(copy_blocks_kernel<uint16_t>, grid, dim3(kThreads), 0, stream, src_base, dst_base,
+                       src_ids_dev, dst_ids_dev, block_bytes, (int32_t)chunks, chunk_bytes / 2);
+  }
+  FLP_TRY_HIP(hipGetLastError());
+  return FLP_OK;
+}

@@ -43,3 +43,72 @@ def close(got, ref, rtol, atol):
 
 
 TOL = {"f32": (1e-4, 1e-5), "f16": (2e-3, 1e-2), "bf16": (2e-3, 1e-2)}
+
+
+# ------------------------------------------------------------------ GPU plumbing (torch = memory only)
+def to_dev(a, pin=False):
+    import torch
+    a = np.ascontiguousarray(a)
+    t = torch.from_numpy(a.view(np.int16) if a.dtype == np.uint16 else a)
+    if pin:
+        return t.pin_memory()
+    return t.cuda()
+
+
+def to_np(t, like_dtype):
+    a = t.detach().cpu().numpy()
+    return a.view(np.uint16) if like_dtype == np.uint16 else a
+
+
+class GpuStep:
+    """Uploads a synthetic Step and owns the flpool handle over torch-allocated tiers."""
+
+    def __init__(self, step, dev_img, host_img):
+        import torch
+        from paper_2505_03756_amd import flpool
+        cfg = step.cfg
+        self.step, self.cfg = step, cfg
+        self.sd = wl.storage_dtype(cfg.dtype)
+        self.dev = to_dev(dev_img)
+        self.host = to_dev(host_img, pin=True)
+        self.pool = flpool.Pool(cfg.dtype, cfg.n_kv_heads, cfg.head_dim, dev_img.shape[0], host_img.shape[0],
+                                block_tokens=cfg.block_tokens, dev=self.dev, host=self.host)
+        self.kv_tables = to_dev(step.kv_tables)
+        self.lora_tables = to_dev(step.lora_tables)
+        self.token_adapter = to_dev(step.token_adapter)
+        self.rank = to_dev(step.rank)
+        self.scale = to_dev(step.scale)
+        self.proj = {name: {k: to_dev(getattr(pr, k)) for k in ("a_tab_off", "a_row_base", "b_tab_off", "b_row_base")}
+                     for name, pr in step.proj.items()}
+        self.acts = {k: to_dev(v) for k, v in step.acts.items()}
+        self.torch = torch
+
+    def dev_image(self):
+        self.torch.cuda.synchronize()
+        return to_np(self.dev, self.sd)
+
+    def host_image(self):
+        self.torch.cuda.synchronize()
+        return to_np(self.host, self.sd)
+
+    def lora(self, names, x_key="x"):
+        """Run flp_lora_apply_paged for the named projections on copies of the base terms; returns storage arrays."""
+        st = self.step
+        ys = {n: self.acts["base_" + n].clone() for n in names}
+        projs = [dict(y=ys[n], d_out=st.proj[n].d_out, **self.proj[n]) for n in names]
+        x = self.acts[x_key]
+        self.pool.lora_apply_paged(x, self.token_adapter, self.rank, self.scale, self.lora_tables, projs,
+                                   n_tokens=st.n_tokens, d_in=x.shape[1], n_adapters=len(st.rank),
+                                   max_rank=int(max(1, st.rank.max())))
+        self.torch.cuda.synchronize()
+        return {n: to_np(ys[n], self.sd) for n in names}
+
+    def attention(self, append=True, q_key="q"):
+        st, cfg = self.step, self.cfg
+        q = self.acts[q_key]
+        out = self.torch.zeros_like(q)
+        self.pool.paged_prefix_attention(q, out, st.cu_new, st.prefix_len, self.kv_tables, cfg.n_q_heads,
+                                         k_new=self.acts["k_new"] if append else None,
+                                         v_new=self.acts["v_new"] if append else None)
+        self.torch.cuda.synchronize()
+        return to_np(out, self.sd)

@@ -1,0 +1,187 @@
+"""Host-side checks of the C-ABI library that need no GPU: it loads, exports what the header
+declares, and its free lists / argument validation agree with the oracle's allocator model."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+import oracle
+from oracle import OracleError
+from paper_2505_03756_amd import flpool
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _host_pool(n_dev=64, n_host=16, dtype="f16", n_kv=2, d=64):
+    be = 2 * 16 * n_kv * d
+    sd = np.float32 if dtype == "f32" else np.uint16
+    # over-allocate so that a 256-byte aligned base exists inside each buffer
+    dev = np.zeros(n_dev * be + 256, sd)
+    host = np.zeros(n_host * be + 256, sd)
+
+    def aligned(a):
+        return (a.ctypes.data + 255) & ~255
+    p = flpool.Pool(dtype, n_kv, d, n_dev, n_host, dev=aligned(dev), host=aligned(host))
+    p._bufs = (dev, host)
+    return p
+
+
+def test_library_exports_every_declared_symbol():
+    lib = flpool.load()
+    header = open(os.path.join(ROOT, "include", "flpool.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b(flp_[a-z_0-9]+)\s*\(", header))
+    assert declared, "no declarations parsed"
+    for name in declared:
+        assert hasattr(lib, name), name
+    assert declared == set(flpool.EXPORTS)
+    assert b"flpool" in lib.flp_version()
+
+
+def test_struct_sizes_match_header_layout():
+    # natural alignment of the C structs in include/flpool.h
+    assert C.sizeof(flpool.PoolConfig) == 48
+    assert C.sizeof(flpool.AttnBatch) == 16 + 7 * 8
+    assert C.sizeof(flpool.LoraProj) == 16 + 6 * 8
+    assert C.sizeof(flpool.LoraBatch) == 32 + 5 * 8 + 4 * C.sizeof(flpool.LoraProj)
+
+
+def test_alloc_free_match_oracle_model_bit_exactly():
+    rng = np.random.default_rng(100)
+    for tier, n in ((0, 64), (1, 16)):
+        pool = _host_pool()
+        model = oracle.Allocator(n)
+        held = []
+        for _ in range(1500):
+            if rng.random() < 0.55:
+                k = int(rng.integers(0, 7))
+                try:
+                    want = model.alloc(k)
+                except OracleError as e:
+                    with pytest.raises(flpool.FlpError) as g:
+                        pool.alloc(k, tier)
+                    assert g.value.code == e.code == flpool.FLP_ENOSPC
+                    continue
+                got = pool.alloc(k, tier)
+                assert np.array_equal(got, want)
+                held += list(got)
+            elif held:
+                k = int(rng.integers(1, min(len(held), 5) + 1))
+                pick = [held.pop(int(rng.integers(0, len(held)))) for _ in range(k)]
+                model.free(pick)
+                pool.free(pick, tier)
+            assert pool.num_free(tier) == model.num_free
+        pool.close()
+
+
+def test_shuffled_free_list_recipe():
+    # "random block permutation": allocate everything, free in a seeded shuffled order,
+    # then allocations come back in the reverse of that order - identical in model and library
+    rng = np.random.default_rng(101)
+    pool = _host_pool()
+    model = oracle.Allocator(64)
+    order = rng.permutation(64).astype(np.int32)
+    for a in (pool, model):
+        a.alloc(64)
+        a.free(order)
+    got, want = pool.alloc(20), model.alloc(20)
+    assert np.array_equal(got, want) and np.array_equal(got, order[::-1][:20])
+
+
+def test_alloc_free_error_codes_leave_state_unchanged():
+    pool = _host_pool(n_dev=8)
+    ids = pool.alloc(6)
+    with pytest.raises(flpool.FlpError) as e:
+        pool.alloc(3)
+    assert e.value.code == flpool.FLP_ENOSPC and pool.num_free() == 2
+    for bad, code in (([8], flpool.FLP_ERANGE), ([-1], flpool.FLP_ERANGE), ([7], flpool.FLP_EDUP),
+                      ([ids[0], ids[1], ids[0]], flpool.FLP_EDUP)):
+        with pytest.raises(flpool.FlpError) as e:
+            pool.free(bad)
+        assert e.value.code == code
+        assert pool.num_free() == 2
+    with pytest.raises(flpool.FlpError) as e:
+        pool.alloc(-1)
+    assert e.value.code == flpool.FLP_EINVAL
+    pool.free(ids)
+    assert pool.num_free() == 8
+    assert "flp_pool" in str(e.value)
+
+
+def test_swap_list_validation_without_touching_memory():
+    pool = _host_pool(n_dev=8, n_host=4)
+    for fn, a, b, code in (
+            (pool.swap_in, [0, 1], [3, 3], flpool.FLP_EDUP),       # duplicate destination (device side)
+            (pool.swap_in, [4], [0], flpool.FLP_ERANGE),           # host id out of range
+            (pool.swap_in, [0], [8], flpool.FLP_ERANGE),
+            (pool.swap_out, [0, 1], [2, 2], flpool.FLP_EDUP),      # duplicate destination (host side)
+            (pool.swap_out, [8], [0], flpool.FLP_ERANGE),
+            (pool.swap_out, [0], [-1], flpool.FLP_ERANGE)):
+        with pytest.raises(flpool.FlpError) as e:
+            fn(a, b, stream=0)
+        assert e.value.code == code
+    pool.swap_in([], [], stream=0)          # empty list: success, nothing enqueued
+    pool.swap_out([], [], stream=0)
+    with pytest.raises(flpool.FlpError) as e:
+        pool.swap_in([0, 1], [2], stream=0)
+    assert e.value.code == flpool.FLP_EINVAL
+
+
+def test_attention_argument_checks():
+    pool = _host_pool(n_kv=2, d=64)
+    fake = 0x1000                      # never dereferenced: the checks fail first
+    tables = np.zeros((2, 3), np.int32)
+    with pytest.raises(flpool.FlpError) as e:    # 40 + 9 positions > 3 blocks * 16
+        pool.paged_prefix_attention(fake, fake, [0, 4, 13], [10, 40], tables.ctypes.data, 4, max_blocks=3, stream=0)
+    assert e.value.code == flpool.FLP_ERANGE
+    with pytest.raises(flpool.FlpError) as e:    # 3 query heads over 2 kv heads
+        pool.paged_prefix_attention(fake, fake, [0, 4], [10], tables.ctypes.data, 3, max_blocks=3, stream=0)
+    assert e.value.code == flpool.FLP_EINVAL
+    with pytest.raises(flpool.FlpError) as e:    # cu_new decreasing
+        pool.paged_prefix_attention(fake, fake, [0, 4, 2], [1, 1], tables.ctypes.data, 4, max_blocks=3, stream=0)
+    assert e.value.code == flpool.FLP_EINVAL
+    with pytest.raises(flpool.FlpError) as e:    # misaligned q
+        pool.paged_prefix_attention(fake + 2, fake, [0, 4], [1], tables.ctypes.data, 4, max_blocks=3, stream=0)
+    assert e.value.code == flpool.FLP_EINVAL
+    with pytest.raises(flpool.FlpError) as e:    # append without v_new
+        pool.kv_append(fake, None, [0, 4], [1], tables.ctypes.data, max_blocks=3, stream=0)
+    assert e.value.code == flpool.FLP_EINVAL
+    odd = flpool.Pool("f16", 2, 80, 4, 0, dev=pool.base(0), host=None)
+    with pytest.raises(flpool.FlpError) as e:
+        odd.paged_prefix_attention(fake, fake, [0, 1], [1], tables.ctypes.data, 2, max_blocks=3, stream=0)
+    assert e.value.code == flpool.FLP_ENOTSUP
+
+
+def test_lora_argument_checks():
+    pool = _host_pool(n_kv=2, d=64)            # block = 4096 elements
+    fake = 0x1000
+    proj = dict(y=fake, d_out=64, a_tab_off=fake, a_row_base=fake, b_tab_off=fake, b_row_base=fake)
+    kw = dict(x=fake, token_adapter=fake, rank=fake, scale=fake, block_tables=fake, n_tokens=4, d_in=64,
+              n_adapters=2, max_rank=8, stream=0)
+    with pytest.raises(flpool.FlpError) as e:
+        pool.lora_apply_paged(projs=[proj], **{**kw, "max_rank": 65})
+    assert e.value.code == flpool.FLP_ERANGE
+    with pytest.raises(flpool.FlpError) as e:
+        pool.lora_apply_paged(projs=[proj], **{**kw, "d_in": 8192})     # a page-row longer than a block
+    assert e.value.code == flpool.FLP_EINVAL
+    with pytest.raises(flpool.FlpError) as e:
+        pool.lora_apply_paged(projs=[dict(proj, d_out=60)], **kw)       # not a multiple of 8 elements
+    assert e.value.code == flpool.FLP_EINVAL
+    with pytest.raises(flpool.FlpError) as e:
+        pool.lora_apply_paged(projs=[dict(proj, y=None)], **kw)
+    assert e.value.code == flpool.FLP_EINVAL
+    with pytest.raises(flpool.FlpError) as e:
+        pool.lora_apply_paged(projs=[proj] * 5, **kw)
+    assert e.value.code == flpool.FLP_EINVAL
+    pool.lora_apply_paged(projs=[proj], **{**kw, "n_tokens": 0})        # empty batch: success
+
+
+def test_pool_create_rejects_bad_geometry():
+    with pytest.raises(flpool.FlpError) as e:
+        flpool.Pool("f16", 0, 64, 4, 0, dev=0x1000)
+    assert e.value.code == flpool.FLP_EINVAL
+    with pytest.raises(flpool.FlpError) as e:
+        flpool.Pool("f16", 2, 64, 4, 0, dev=0x1010)       # not 256-byte aligned
+    assert e.value.code == flpool.FLP_EINVAL

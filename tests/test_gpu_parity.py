@@ -1,0 +1,202 @@
+"""GPU parity: the HIP path through the C ABI against the CPU oracle, element by element."""
+import numpy as np
+import pytest
+
+import oracle
+from helpers import TOL, GpuStep, build_pools, close, resident_pool, to_dev, to_np
+from paper_2505_03756_amd import flpool
+from paper_2505_03756_amd import workload as wl
+
+pytestmark = pytest.mark.gpu
+
+
+def small_cfg(dtype, **kw):
+    base = dict(name="small_" + dtype, dtype=dtype, hidden=512, n_q_heads=4, n_kv_heads=4, head_dim=128,
+                n_dev_blocks=400, n_host_blocks=512, n_adapters=6, ranks=(8, 16, 32), projections=("q", "k", "v", "o"),
+                n_seqs=7, prefix_range=(0, 300), new_range=(1, 70), swap_in_frac=0.4, seed=77)
+    base.update(kw)
+    return wl.LayerConfig(**base)
+
+
+CASES = {
+    "tiny": lambda: wl.config("tiny"),
+    "f16_prefill": lambda: small_cfg("f16"),
+    "bf16_decode": lambda: small_cfg("bf16", n_seqs=19, prefix_range=(1, 700), new_range=(1, 1), decode_frac=1.0,
+                                     n_dev_blocks=1200, seed=78),
+    "bf16_gqa_mixed": lambda: small_cfg("bf16", n_q_heads=8, n_kv_heads=2, hidden=1024, decode_frac=0.5,
+                                        prefix_range=(0, 500), seed=79),
+    "f16_d64": lambda: small_cfg("f16", head_dim=64, n_q_heads=8, n_kv_heads=8, seed=80),
+    "f32_d128": lambda: small_cfg("f32", n_seqs=4, prefix_range=(0, 120), new_range=(1, 40), seed=81),
+}
+
+
+@pytest.fixture(scope="module", params=list(CASES))
+def case(request):
+    cfg = CASES[request.param]()
+    step = wl.make_step(cfg)
+    print("\n[case %s] T=%d S=%d dtype=%s" % (request.param, step.n_tokens, cfg.n_seqs, cfg.dtype), flush=True)
+    return step
+
+
+def test_swap_in_out_bit_exact(case):
+    step, cfg = case, case.cfg
+    dev0, host0 = build_pools(step, poison_rest=True)
+    g = GpuStep(step, dev0, host0)
+    # oracle
+    dev_ref, host_ref = dev0.copy(), host0.copy()
+    oracle.swap(host_ref, dev_ref, step.swap_out_dev, step.swap_out_host)
+    oracle.swap(dev_ref, host_ref, step.swap_in_host, step.swap_in_dev)
+    # library: swap-out first, then swap-in (the order the paper gives when the device tier is full)
+    g.pool.swap_out(step.swap_out_dev, step.swap_out_host)
+    g.pool.swap_in(step.swap_in_host, step.swap_in_dev)
+    assert np.array_equal(g.dev_image().view(np.uint8), dev_ref.view(np.uint8))
+    assert np.array_equal(g.host_image().view(np.uint8), host_ref.view(np.uint8))
+    # after the swap-in every needed block is resident with its content
+    assert np.array_equal(g.dev_image()[step.content_ids].view(np.uint8), step.content.view(np.uint8))
+
+
+def test_swap_round_trip_every_block():
+    cfg = wl.config("tiny")
+    rng = np.random.default_rng(5)
+    dev0 = rng.standard_normal((cfg.n_dev_blocks, cfg.block_elems)).astype(np.float32)
+    host0 = np.zeros((cfg.n_dev_blocks, cfg.block_elems), np.float32)
+    step = wl.make_step(cfg, with_acts=False)
+    g = GpuStep(step, dev0, host0)
+    ids = np.arange(cfg.n_dev_blocks, dtype=np.int32)
+    perm, back = rng.permutation(ids).astype(np.int32), rng.permutation(ids).astype(np.int32)
+    g.pool.swap_out(ids, perm)
+    assert np.array_equal(g.host_image()[perm], dev0)
+    g.dev.zero_()
+    g.pool.swap_in(perm, back)
+    assert np.array_equal(g.dev_image()[back], dev0)
+
+
+def test_kv_append_bit_exact(case):
+    step, cfg = case, case.cfg
+    dev0 = resident_pool(step)
+    g = GpuStep(step, dev0, np.zeros((1, cfg.block_elems), dev0.dtype))
+    ref = dev0.copy()
+    oracle.kv_append(ref, cfg.dtype, cfg.block_tokens, cfg.n_kv_heads, cfg.head_dim, step.cu_new, step.prefix_len,
+                     step.kv_tables, step.acts["k_new"], step.acts["v_new"])
+    g.pool.kv_append(g.acts["k_new"], g.acts["v_new"], step.cu_new, step.prefix_len, g.kv_tables)
+    assert np.array_equal(g.dev_image().view(np.uint8), ref.view(np.uint8))
+
+
+def test_attention_matches_oracle(case):
+    step, cfg = case, case.cfg
+    dev0 = resident_pool(step)       # fresh blocks hold NaN patterns until the append fills their slots
+    g = GpuStep(step, dev0, np.zeros((1, cfg.block_elems), dev0.dtype))
+    got = wl.dequantize(g.attention(append=True), cfg.dtype).reshape(step.n_tokens, cfg.n_q_heads, cfg.head_dim)
+    ref_pool = dev0.copy()
+    oracle.kv_append(ref_pool, cfg.dtype, cfg.block_tokens, cfg.n_kv_heads, cfg.head_dim, step.cu_new,
+                     step.prefix_len, step.kv_tables, step.acts["k_new"], step.acts["v_new"])
+    want = oracle.paged_attention(ref_pool, cfg.dtype, cfg.block_tokens, cfg.n_kv_heads, cfg.head_dim, cfg.n_q_heads,
+                                  step.cu_new, step.prefix_len, step.kv_tables, step.acts["q"])
+    rtol, atol = TOL[cfg.dtype]
+    ok, worst, nbad = close(got, want, rtol, atol)
+    assert ok, "max err %g, %d elements out of tolerance" % (worst, nbad)
+    # second entry form: K/V already appended, k_new = v_new = NULL
+    got2 = wl.dequantize(g.attention(append=False), cfg.dtype).reshape(got.shape)
+    assert np.array_equal(got, got2)
+
+
+def test_lora_matches_oracle(case):
+    step, cfg = case, case.cfg
+    dev0 = resident_pool(step)
+    g = GpuStep(step, dev0, np.zeros((1, cfg.block_elems), dev0.dtype))
+    rtol, atol = TOL[cfg.dtype]
+    groups = [[p for p in cfg.projections if p in ("q", "k", "v")], [p for p in cfg.projections if p == "o"]]
+    for names in groups:
+        if not names:
+            continue
+        x_key = "x" if names[0] != "o" or cfg.proj_dims("o")[0] == cfg.hidden else "x_%d" % cfg.proj_dims("o")[0]
+        got = g.lora(names, x_key=x_key)
+        for n in names:
+            pr = step.proj[n]
+            want = oracle.lora_apply(dev0, cfg.dtype, step.acts[x_key], step.token_adapter, step.rank, step.scale,
+                                     pr.a_tab_off, pr.a_row_base, pr.b_tab_off, pr.b_row_base, step.lora_tables,
+                                     pr.d_out, y_in=step.acts["base_" + n])
+            ok, worst, nbad = close(wl.dequantize(got[n], cfg.dtype), want, rtol, atol)
+            assert ok, "%s: max err %g, %d elements out of tolerance" % (n, worst, nbad)
+            delta = np.abs(want - wl.dequantize(step.acts["base_" + n], cfg.dtype)).max()
+            assert delta > 10 * atol or cfg.dtype == "f32"      # the test would notice a missing delta
+
+
+def test_segmentation_bit_exact():
+    import torch
+    rng = np.random.default_rng(9)
+    pool = flpool.Pool("f16", 1, 64, 2, 0)
+    for T, n_ad in [(1, 1), (63, 5), (64, 5), (1000, 40), (5000, 300), (20000, 2048), (257, 100)]:
+        ta = rng.integers(-1, n_ad, size=T).astype(np.int32)
+        if T > 100:
+            ta[rng.integers(0, T, size=T // 2)] = rng.integers(0, min(3, n_ad))      # a few heavy adapters
+        seg_adapter, seg_start, perm = oracle.segment(ta, n_ad)
+        d_ta = to_dev(ta)
+        d_nseg = torch.zeros(1, dtype=torch.int32, device="cuda")
+        d_sa = torch.full((n_ad,), -7, dtype=torch.int32, device="cuda")
+        d_ss = torch.full((n_ad + 1,), -7, dtype=torch.int32, device="cuda")
+        d_perm = torch.full((T,), -7, dtype=torch.int32, device="cuda")
+        pool.lora_segment(d_ta, T, n_ad, d_nseg, d_sa, d_ss, d_perm)
+        torch.cuda.synchronize()
+        n = int(d_nseg.item())
+        assert n == len(seg_adapter)
+        assert np.array_equal(d_sa.cpu().numpy()[:n], seg_adapter)
+        assert np.array_equal(d_ss.cpu().numpy()[:n + 1], seg_start)
+        assert np.array_equal(d_perm.cpu().numpy()[:seg_start[n]], perm)
+
+
+def test_degenerate_batches():
+    import torch
+    cfg = small_cfg("f16", n_seqs=5, prefix_range=(64, 64), new_range=(16, 16), seed=90)
+    step = wl.make_step(cfg)
+    # sequences with zero new tokens, zero prefix, a single token, a prefix ending on a block boundary
+    step.prefix_len[:] = [0, 16, 33, 0, 48]
+    step.new_len[:] = [1, 0, 5, 17, 16]
+    step.cu_new[1:] = np.cumsum(step.new_len)
+    T = int(step.cu_new[-1])
+    for k in ("q", "k_new", "v_new"):
+        step.acts[k] = step.acts[k][:T].copy()
+    dev0 = resident_pool(step)
+    dev0[step.content_ids] = wl.quantize(np.random.default_rng(1).standard_normal(step.content.shape), "f16")
+    g = GpuStep(step, dev0, np.zeros((1, cfg.block_elems), dev0.dtype))
+    got = wl.dequantize(g.attention(append=True), "f16").reshape(T, cfg.n_q_heads, cfg.head_dim)
+    ref_pool = dev0.copy()
+    oracle.kv_append(ref_pool, "f16", 16, cfg.n_kv_heads, cfg.head_dim, step.cu_new, step.prefix_len, step.kv_tables,
+                     step.acts["k_new"], step.acts["v_new"])
+    want = oracle.paged_attention(ref_pool, "f16", 16, cfg.n_kv_heads, cfg.head_dim, cfg.n_q_heads, step.cu_new,
+                                  step.prefix_len, step.kv_tables, step.acts["q"])
+    ok, worst, nbad = close(got, want, *TOL["f16"])
+    assert ok, (worst, nbad)
+    # P = 0, N = 1: the output is exactly v0 (softmax over a single key)
+    v0 = wl.dequantize(step.acts["v_new"][0], "f16").reshape(cfg.n_kv_heads, cfg.head_dim)
+    assert np.array_equal(got[0], v0)
+    # empty batch and all-empty sequences enqueue nothing and succeed
+    g.pool.paged_prefix_attention(g.acts["q"], g.acts["q"], [0], [], g.kv_tables, cfg.n_q_heads)
+    g.pool.paged_prefix_attention(g.acts["q"], g.acts["q"], [0, 0, 0], [3, 4], g.kv_tables, cfg.n_q_heads)
+    g.pool.swap_in([], [])
+    torch.cuda.synchronize()
+
+
+def test_lora_no_adapter_tokens_and_zero_b():
+    cfg = small_cfg("bf16", seed=91)
+    step = wl.make_step(cfg)
+    step.token_adapter[::3] = -1
+    dev0 = resident_pool(step)
+    g = GpuStep(step, dev0, np.zeros((1, cfg.block_elems), dev0.dtype))
+    got = g.lora(["q"])["q"]
+    none = np.flatnonzero(step.token_adapter < 0)
+    assert np.array_equal(got[none], step.acts["base_q"][none])           # untouched rows, bit for bit
+    pr = step.proj["q"]
+    want = oracle.lora_apply(dev0, "bf16", step.acts["x"], step.token_adapter, step.rank, step.scale, pr.a_tab_off,
+                             pr.a_row_base, pr.b_tab_off, pr.b_row_base, step.lora_tables, pr.d_out,
+                             y_in=step.acts["base_q"])
+    ok, worst, nbad = close(wl.dequantize(got, "bf16"), want, *TOL["bf16"])
+    assert ok, (worst, nbad)
+    # B = 0 for every adapter: y is the base term exactly
+    zero = dev0.copy()
+    for a in np.flatnonzero(step.rank):
+        for rho in range(step.rank[a]):
+            oracle.lora_write_row(zero, "bf16", step.lora_tables[pr.b_tab_off[a]:], pr.b_row_base[a] + rho,
+                                  np.zeros(pr.d_out, np.uint16))
+    g2 = GpuStep(step, zero, np.zeros((1, cfg.block_elems), dev0.dtype))
+    assert np.array_equal(g2.lora(["q"])["q"], step.acts["base_q"])
