@@ -70,17 +70,16 @@ struct StagedSeqs {
   const void* units = nullptr;
 };
 
-template <typename Unit>
-flp_status stage_seqs(flp_pool* p, const flp_attn_batch* b, const std::vector<Unit>& units, hipStream_t stream,
+flp_status stage_seqs(flp_pool* p, const flp_attn_batch* b, const void* units, size_t unit_bytes, hipStream_t stream,
                       StagedSeqs* out) {
   const size_t S = (size_t)b->n_seqs;
   const size_t off_pl = (S + 1) * 4, off_units = ((off_pl + S * 4 + 31) / 32) * 32;
-  const size_t bytes = off_units + units.size() * sizeof(Unit);
+  const size_t bytes = off_units + unit_bytes;
   FLP_TRY(flp_stage_acquire(p, bytes, &out->slot));
   uint8_t* h = (uint8_t*)out->slot->host;
   memcpy(h, b->cu_new, (S + 1) * 4);
   memcpy(h + off_pl, b->prefix_len, S * 4);
-  if (!units.empty()) memcpy(h + off_units, units.data(), units.size() * sizeof(Unit));
+  if (unit_bytes) memcpy(h + off_units, units, unit_bytes);
   FLP_TRY(flp_stage_upload(out->slot, bytes, stream));
   const uint8_t* d = (const uint8_t*)out->slot->dev;
   out->cu_new = (const int32_t*)d;
@@ -127,7 +126,7 @@ flp_status append_locked(flp_pool* p, const flp_attn_batch* b, hipStream_t strea
   }
   if (units.empty()) return FLP_OK;
   StagedSeqs st;
-  FLP_TRY(stage_seqs(p, b, units, stream, &st));
+  FLP_TRY(stage_seqs(p, b, units.data(), units.size() * sizeof(FlpAppendUnit), stream, &st));
   FlpAttnArgs a = make_args(p, b, st);
   flp_status s1 = flp_launch_kv_append(p->cfg.dtype, p->cfg.head_dim, a, (const FlpAppendUnit*)st.units,
                                        (int32_t)units.size(), stream);
@@ -150,33 +149,71 @@ extern "C" flp_status flp_paged_prefix_attention(flp_pool* p, const flp_attn_bat
   hipStream_t stream = (hipStream_t)hip_stream;
   if (with_append) FLP_TRY(append_locked(p, b, stream));
 
-  // work units: runs of up to 4 new tokens of one sequence, heaviest first so that the
-  // long contexts start early and the short ones fill the tail
+  // Two kinds of work.  Sequences with at least 8 query rows per kv head (prefill, or decode
+  // under grouped-query attention) on a 16-bit pool with head_dim 128 go to the matrix-core
+  // kernel in tiles of 128 rows; everything else (fp32, head_dim 64, single-row decode) goes to
+  // the row-streaming kernel in runs of up to 4 tokens.  Both lists are ordered heaviest first.
+  const bool mfma_ok = p->cfg.dtype != FLP_F32 && p->cfg.head_dim == 128;
+  const int G = b->n_q_heads / p->cfg.n_kv_heads;
+  const int n_kv = p->cfg.n_kv_heads;
+  std::vector<int32_t> seq_order(b->n_seqs);
+  std::iota(seq_order.begin(), seq_order.end(), 0);
+  auto seq_cost = [&](int32_t i) {
+    int64_t n = b->cu_new[i + 1] - b->cu_new[i];
+    return n * (2 * (int64_t)b->prefix_len[i] + n);
+  };
+  std::stable_sort(seq_order.begin(), seq_order.end(), [&](int32_t x, int32_t y) { return seq_cost(x) > seq_cost(y); });
+
   std::vector<FlpAttnUnit> units;
   std::vector<int64_t> cost;
   constexpr int kTokPerUnit = 4;
-  for (int32_t i = 0; i < b->n_seqs; ++i) {
+  // matrix-core items: the row tiles of one (sequence, kv head) are dealt to ONE of 8 queues and
+  // the queues are interleaved, so that under round-robin dispatch of workgroups over the 8
+  // XCDs the tiles that re-read the same K/V run on the same XCD and share its L2.
+  std::vector<FlpMfmaItem> queue[8];
+  int next_q = 0;
+  for (int32_t i : seq_order) {
     const int32_t n = b->cu_new[i + 1] - b->cu_new[i];
-    for (int32_t j0 = 0; j0 < n; j0 += kTokPerUnit) {
-      FlpAttnUnit u{i, j0, std::min(kTokPerUnit, n - j0), 0};
-      units.push_back(u);
-      cost.push_back((int64_t)u.n_tok * (b->prefix_len[i] + j0 + u.n_tok));
+    if (n <= 0) continue;
+    if (mfma_ok && (int64_t)G * n >= 8) {
+      const int32_t R = G * n;
+      for (int g = 0; g < n_kv; ++g) {
+        for (int32_t r0 = 0; r0 < R; r0 += kMfmaRowsPerItem)
+          queue[next_q].push_back(FlpMfmaItem{i, g, r0, std::min<int32_t>(kMfmaRowsPerItem, R - r0)});
+        next_q = (next_q + 1) & 7;
+      }
+    } else {
+      for (int32_t j0 = 0; j0 < n; j0 += kTokPerUnit) {
+        FlpAttnUnit u{i, j0, std::min(kTokPerUnit, n - j0), 0};
+        units.push_back(u);
+        cost.push_back((int64_t)u.n_tok * (b->prefix_len[i] + j0 + u.n_tok));
+      }
     }
   }
-  if (units.empty()) return FLP_OK;
   std::vector<int32_t> order(units.size());
   std::iota(order.begin(), order.end(), 0);
   std::stable_sort(order.begin(), order.end(), [&](int32_t x, int32_t y) { return cost[x] > cost[y]; });
-  std::vector<FlpAttnUnit> sorted(units.size());
-  for (size_t k = 0; k < order.size(); ++k) sorted[k] = units[order[k]];
+  size_t qmax = 0;
+  for (auto& q : queue) qmax = std::max(qmax, q.size());
+  const size_t n_items = qmax * 8;
+  if (units.empty() && n_items == 0) return FLP_OK;
+
+  std::vector<uint8_t> blob(units.size() * sizeof(FlpAttnUnit) + n_items * sizeof(FlpMfmaItem));
+  FlpAttnUnit* hu = (FlpAttnUnit*)blob.data();
+  for (size_t k = 0; k < order.size(); ++k) hu[k] = units[order[k]];
+  FlpMfmaItem* hi = (FlpMfmaItem*)(blob.data() + units.size() * sizeof(FlpAttnUnit));
+  for (size_t s = 0; s < qmax; ++s)
+    for (int x = 0; x < 8; ++x) hi[8 * s + x] = s < queue[x].size() ? queue[x][s] : FlpMfmaItem{0, 0, 0, 0};
 
   StagedSeqs st;
-  FLP_TRY(stage_seqs(p, b, sorted, stream, &st));
+  FLP_TRY(stage_seqs(p, b, blob.data(), blob.size(), stream, &st));
   FlpAttnArgs a = make_args(p, b, st);
-  flp_status s1 = flp_launch_attn_rows(p->cfg.dtype, p->cfg.head_dim, a, (const FlpAttnUnit*)st.units,
-                                       (int32_t)sorted.size(), stream);
+  const FlpAttnUnit* du = (const FlpAttnUnit*)st.units;
+  const FlpMfmaItem* di = (const FlpMfmaItem*)((const uint8_t*)st.units + units.size() * sizeof(FlpAttnUnit));
+  flp_status s0 = flp_launch_attn_mfma(p->cfg.dtype, a, di, (int32_t)n_items, stream);
+  flp_status s1 = flp_launch_attn_rows(p->cfg.dtype, p->cfg.head_dim, a, du, (int32_t)units.size(), stream);
   flp_status s2 = flp_stage_release(st.slot, stream);
-  return s1 != FLP_OK ? s1 : s2;
+  return s0 != FLP_OK ? s0 : (s1 != FLP_OK ? s1 : s2);
 }
 
 // ------------------------------------------------------------------------------- LoRA

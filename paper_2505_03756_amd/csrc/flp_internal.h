@@ -85,6 +85,10 @@ struct FlpAttnUnit {     // new tokens [j0, j0+n_tok) of sequence `seq`
   int32_t seq, j0, n_tok, pad;
 };
 
+struct FlpMfmaItem {     // query rows [r0, r0+n_rows) of (sequence, kv head g); n_rows == 0: padding
+  int32_t seq, g, r0, n_rows;
+};
+
 struct FlpAttnArgs {
   uint8_t* pool;
   int64_t block_elems;
@@ -104,6 +108,10 @@ flp_status flp_launch_kv_append(int dtype, int head_dim, const FlpAttnArgs& a, c
                                 int32_t n_units, hipStream_t stream);
 flp_status flp_launch_attn_rows(int dtype, int head_dim, const FlpAttnArgs& a, const FlpAttnUnit* units_dev,
                                 int32_t n_units, hipStream_t stream);
+
+flp_status flp_launch_attn_mfma(int dtype, const FlpAttnArgs& a, const FlpMfmaItem* items_dev, int32_t n_items,
+                                hipStream_t stream);
+constexpr int kMfmaRowsPerItem = 128;
 
 struct FlpLoraArgs {
   const uint8_t* pool;
