@@ -73,7 +73,7 @@ __device__ __forceinline__ V as_vec(u32x4 r) {
 __device__ __forceinline__ int key_of_row(int m) { return (m & 0x13) | ((m & 4) << 1) | ((m & 8) >> 1); }
 
 template <typename M, int NRT>
-__global__ __launch_bounds__(256) void attn_mfma_kernel(FlpAttnArgs a, const FlpMfmaItem* __restrict__ items) {
+__global__ __launch_bounds__(256, 2) void attn_mfma_kernel(FlpAttnArgs a, const FlpMfmaItem* __restrict__ items) {
   typedef typename M::vec vec;
   __shared__ __attribute__((aligned(16))) uint8_t smem[2 * kTileBytes];
 
@@ -184,17 +184,22 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(FlpAttnArgs a, const Flp
       // ---- S^T = K Q^T for the tile's two 32-key sub-tiles
       f32x16 S[2][NRT];
 #pragma unroll
-      for (int st = 0; st < 2; ++st) {
+      for (int st = 0; st < 2; ++st)
 #pragma unroll
         for (int nt = 0; nt < NRT; ++nt)
 #pragma unroll
           for (int i = 0; i < 16; ++i) S[st][nt][i] = 0.f;
-        const uint8_t* krowp = buf + (32 * st + krow) * 256;
+      const uint8_t* krowp = buf + krow * 256;
 #pragma unroll
-        for (int kk = 0; kk < 8; ++kk) {
-          vec ka = as_vec<vec>(*reinterpret_cast<const u32x4*>(krowp + (((2 * kk + hf) ^ a_swz) << 4)));
+      for (int kk = 0; kk < 8; ++kk) {
+        const int coff = ((2 * kk + hf) ^ a_swz) << 4;
+        // the two sub-tiles are independent accumulation chains: alternate them
+        vec ka0 = as_vec<vec>(*reinterpret_cast<const u32x4*>(krowp + coff));
+        vec ka1 = as_vec<vec>(*reinterpret_cast<const u32x4*>(krowp + 32 * 256 + coff));
 #pragma unroll
-          for (int nt = 0; nt < NRT; ++nt) S[st][nt] = M::mfma(ka, qf[nt][kk], S[st][nt]);
+        for (int nt = 0; nt < NRT; ++nt) {
+          S[0][nt] = M::mfma(ka0, qf[nt][kk], S[0][nt]);
+          S[1][nt] = M::mfma(ka1, qf[nt][kk], S[1][nt]);
         }
       }
       // ---- causal mask on the tiles that reach past the first row's position
@@ -221,29 +226,34 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(FlpAttnArgs a, const Flp
 #pragma unroll
           for (int i = 0; i < 16; ++i) tmax = fmaxf(tmax, S[st][nt][i]);
         tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
-        const float m_new = fmaxf(mrow[nt], tmax);
-        const float alpha = exp2f((mrow[nt] - m_new) * c);
-        const float mc = m_new * c;
-        mrow[nt] = m_new;
+        // The running maximum is only raised when some row of the wave has outgrown it by
+        // more than 2^8: until then the weights are taken relative to the old maximum (they
+        // stay below 256, exact in fp32 and well inside the 16-bit range), which spares the
+        // rescaling of the 64 accumulator registers on almost every tile.
+        if (__builtin_amdgcn_ballot_w64((tmax - mrow[nt]) * c > 8.f)) {
+          const float m_new = fmaxf(mrow[nt], tmax);
+          const float alpha = __builtin_amdgcn_exp2f((mrow[nt] - m_new) * c);
+          mrow[nt] = m_new;
+          lrow[nt] *= alpha;
+#pragma unroll
+          for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) O[nt][dt][i] *= alpha;
+        }
+        const float mc = mrow[nt] * c;
         float psum = 0.f;
 #pragma unroll
         for (int st = 0; st < 2; ++st) {
           float p[16];
 #pragma unroll
           for (int i = 0; i < 16; ++i) {
-            p[i] = exp2f(fmaf(S[st][nt][i], c, -mc));
+            p[i] = __builtin_amdgcn_exp2f(fmaf(S[st][nt][i], c, -mc));
             psum += p[i];
           }
           pb[st][nt][0] = M::pack(p);
           pb[st][nt][1] = M::pack(p + 8);
         }
-        lrow[nt] = lrow[nt] * alpha + psum;
-        if (__builtin_amdgcn_ballot_w64(alpha != 1.f)) {
-#pragma unroll
-          for (int dt = 0; dt < 4; ++dt)
-#pragma unroll
-            for (int i = 0; i < 16; ++i) O[nt][dt][i] *= alpha;
-        }
+        lrow[nt] += psum;
       }
       // ---- O^T += V^T P^T, one pool block (16 keys) per instruction
 #pragma unroll

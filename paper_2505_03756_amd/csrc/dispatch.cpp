@@ -228,7 +228,7 @@ extern "C" flp_status flp_lora_segment(flp_pool* p, int32_t n_tokens, const int3
     flp_set_error("flp_lora_segment: %d adapters, at most 2048 supported", n_adapters);
     return FLP_ERANGE;
   }
-  return flp_launch_lora_segment(n_tokens, token_adapter, n_adapters, n_seg, seg_adapter, seg_start, perm,
+  return flp_launch_lora_segment(n_tokens, token_adapter, n_adapters, n_seg, seg_adapter, seg_start, perm, 0, nullptr,
                                  (hipStream_t)hip_stream);
 }
 
@@ -274,8 +274,33 @@ extern "C" flp_status flp_lora_apply_paged(flp_pool* p, const flp_lora_batch* b,
   std::lock_guard<std::mutex> lk(p->mu);
   hipStream_t stream = (hipStream_t)hip_stream;
   const size_t T = (size_t)b->n_tokens;
-  const size_t v_bytes = ((T * b->n_proj * b->max_rank * 4) + 255) & ~(size_t)255;
-  const size_t seg_bytes = ((size_t)(2 * b->n_adapters + 2 + 1) * 4 + 255) & ~(size_t)255;
+
+  // Matrix-core path for 16-bit pools when every width is a multiple of the 32-wide tiles;
+  // otherwise the vector-ALU kernels (fp32 pools, odd widths).
+  bool mfma_ok = p->cfg.dtype != FLP_F32 && b->d_in % 32 == 0;
+  int max_dout = 0;
+  for (int q = 0; q < b->n_proj; ++q) {
+    mfma_ok = mfma_ok && b->proj[q].d_out % 32 == 0;
+    max_dout = std::max(max_dout, b->proj[q].d_out);
+  }
+  FlpLoraMfma c{};
+  size_t v_elems = T * b->n_proj * b->max_rank;
+  if (mfma_ok) {
+    c.mt = b->n_tokens >= 2048 ? 2 : 1;
+    const int tm = 16 * c.mt;
+    c.tiles_bound = (int32_t)((T + tm - 1) / tm) + (int32_t)std::min<size_t>((size_t)b->n_adapters, T);
+    // split K until about 2048 workgroups are in flight, in pieces of 128 coefficients
+    int ks = 1;
+    while (ks < 8 && c.tiles_bound * ks < 2048 && b->d_in / (ks * 2) >= 256) ks *= 2;
+    c.k_splits = ks;
+    c.k_per_split = ((b->d_in + ks - 1) / ks + 127) / 128 * 128;
+    c.v_rows = c.tiles_bound * tm;
+    c.cols_per_slab = max_dout >= 2048 ? 256 : 128;
+    const int rp = 16 * ((b->max_rank + 15) / 16);
+    v_elems = (size_t)ks * c.v_rows * b->n_proj * rp;
+  }
+  const size_t v_bytes = (v_elems * 4 + 255) & ~(size_t)255;
+  const size_t seg_bytes = ((size_t)(3 * b->n_adapters + 4) * 4 + 255) & ~(size_t)255;
   const size_t perm_bytes = (T * 4 + 255) & ~(size_t)255;
   void* ws = nullptr;
   FLP_TRY(flp_workspace(p, v_bytes + seg_bytes + perm_bytes, &ws));
@@ -299,6 +324,10 @@ extern "C" flp_status flp_lora_apply_paged(flp_pool* p, const flp_lora_batch* b,
   a.n_seg = (int32_t*)(w + v_bytes);
   a.seg_adapter = a.n_seg + 1;
   a.seg_start = a.seg_adapter + b->n_adapters;
+  a.tile_start = a.seg_start + b->n_adapters + 1;
   a.perm = (int32_t*)(w + v_bytes + seg_bytes);
-  return flp_launch_lora_simple(p->cfg.dtype, a, stream);
+  if (!mfma_ok) return flp_launch_lora_simple(p->cfg.dtype, a, stream);
+  FLP_TRY(flp_launch_lora_segment(a.T, a.token_adapter, a.n_adapters, a.n_seg, a.seg_adapter, a.seg_start, a.perm,
+                                  16 * c.mt, a.tile_start, stream));
+  return flp_launch_lora_mfma(p->cfg.dtype, a, c, stream);
 }

@@ -46,7 +46,7 @@ struct FlpStageSlot {
   bool in_flight = false;
 };
 
-constexpr int kStageSlots = 8;
+constexpr int kStageSlots = 16;
 
 struct flp_pool {
   flp_pool_config cfg{};
@@ -77,6 +77,8 @@ flp_status flp_workspace(flp_pool* pool, size_t bytes, void** out);
 flp_status flp_launch_copy_blocks(const uint8_t* src_base, uint8_t* dst_base, const int32_t* src_ids_dev,
                                   const int32_t* dst_ids_dev, int32_t n, int64_t block_bytes,
                                   hipStream_t stream);
+
+flp_status flp_launch_stage_copy(const void* src_pinned, void* dst_dev, size_t bytes, hipStream_t stream);
 
 struct FlpAppendUnit {   // the slots [s0, s1) of block `blk_idx` of sequence `seq`
   int32_t seq, blk_idx, s0, s1, t_first, pad0, pad1, pad2;
@@ -130,8 +132,19 @@ struct FlpLoraArgs {
   int32_t* seg_adapter;
   int32_t* seg_start;
   int32_t* perm;
+  int32_t* tile_start;         // [n_seg + 1] first tile of each segment (matrix-core kernels)
+};
+
+struct FlpLoraMfma {
+  int32_t mt;                  // 16-token tiles per work item (1 or 2)
+  int32_t k_splits, k_per_split;
+  int32_t v_rows;              // rows of one split's partial v buffer (= tiles_bound * 16 * mt)
+  int32_t cols_per_slab;
+  int32_t tiles_bound;         // host-side upper bound of the number of tiles
 };
 
 flp_status flp_launch_lora_segment(int32_t T, const int32_t* token_adapter, int32_t n_adapters, int32_t* n_seg,
-                                   int32_t* seg_adapter, int32_t* seg_start, int32_t* perm, hipStream_t stream);
+                                   int32_t* seg_adapter, int32_t* seg_start, int32_t* perm, int32_t tm,
+                                   int32_t* tile_start, hipStream_t stream);
+flp_status flp_launch_lora_mfma(int dtype, const FlpLoraArgs& a, const FlpLoraMfma& c, hipStream_t stream);
 flp_status flp_launch_lora_simple(int dtype, const FlpLoraArgs& a, hipStream_t stream);

@@ -1,0 +1,324 @@
+// Batched heterogeneous LoRA on the matrix cores, for 16-bit pools (paper Eq. 1 / Eq. 2 in
+// row-vector form, y = base + s (x A^T) B; section 2.1: tokens of different adapters share
+// one batch; section 4.3: adapters live in pool blocks as rank rows).
+//
+// Tokens are first grouped by adapter (lora.hip); a tile is up to 16*MT consecutive tokens
+// of one adapter.  Both kernels read their operands straight from global memory in MFMA
+// operand layout: the rank-major page rows make 8 consecutive coefficients of one rank one
+// 16-byte run, which is exactly a lane's share of a 16x16x32 operand, so nothing is staged
+// or transposed in LDS and every page byte is fetched once per tile.
+//
+//   shrink  v[t, rho] = sum_c x[t,c] A[rho,c]     M = tokens, N = ranks, K = d_in.  K is
+//           split over the 4 waves of a workgroup (summed in LDS in a fixed order) and over
+//           KS workgroups (partial sums in global memory, added in order by the expand
+//           kernel), so that enough waves are in flight to stream x at HBM rate.
+//   expand  y[t, o] += s sum_rho v[t,rho] B[rho,o]   computed transposed, M = columns,
+//           N = tokens, K = ranks.  v stays fp32: it is split into a 16-bit high part and
+//           a 16-bit remainder that occupy the two halves of the K = 32 contraction (the
+//           B coefficients are fed to both halves).  Two column tiles are interleaved so
+//           that a lane ends up with 8 consecutive columns of one token: y is read and
+//           written in 16-byte pieces.
+#include <hip/hip_runtime.h>
+
+#include "flp_internal.h"
+#include "flp_types.h"
+
+namespace {
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef _Float16 h16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 b16x8 __attribute__((ext_vector_type(8)));
+
+struct LF16 {
+  typedef h16x8 vec;
+  typedef F16 S;
+  static __device__ __forceinline__ f32x4 mfma(vec a, vec b, f32x4 c) {
+    return __builtin_amdgcn_mfma_f32_16x16x32_f16(a, b, c, 0, 0, 0);
+  }
+  static __device__ __forceinline__ void split(float v, _Float16* hi, _Float16* lo) {
+    *hi = (_Float16)v;
+    *lo = (_Float16)(v - (float)*hi);
+  }
+  typedef _Float16 elem;
+};
+struct LBF16 {
+  typedef b16x8 vec;
+  typedef BF16 S;
+  static __device__ __forceinline__ f32x4 mfma(vec a, vec b, f32x4 c) {
+    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
+  }
+  static __device__ __forceinline__ void split(float v, __bf16* hi, __bf16* lo) {
+    *hi = (__bf16)v;
+    *lo = (__bf16)(v - (float)*hi);
+  }
+  typedef __bf16 elem;
+};
+
+template <typename V>
+__device__ __forceinline__ V vec_from(u32x4 r) {
+  V v;
+  __builtin_memcpy(&v, &r, 16);
+  return v;
+}
+
+// tile -> segment: largest s with tile_start[s] <= tile (tile < tile_start[n_seg])
+__device__ __forceinline__ int find_segment(const int32_t* __restrict__ tile_start, int n_seg, int tile) {
+  int lo = 0, hi = n_seg;   // invariant: tile_start[lo] <= tile < tile_start[hi]
+  while (hi - lo > 1) {
+    int mid = (lo + hi) >> 1;
+    if (tile_start[mid] <= tile) lo = mid; else hi = mid;
+  }
+  return lo;
+}
+
+// ------------------------------------------------------------------------------- shrink
+template <typename L, int MT, int NT>
+__global__ __launch_bounds__(256) void lora_shrink_mfma_kernel(FlpLoraArgs a, FlpLoraMfma c) {
+  typedef typename L::vec vec;
+  extern __shared__ float red[];                       // [4 waves][n_acc][64 lanes]
+  const int tile = blockIdx.x, ks = blockIdx.y;
+  const int n_seg = *a.n_seg;
+  if (tile >= a.tile_start[n_seg]) return;
+  const int s = find_segment(a.tile_start, n_seg, tile);
+  const int ad = a.seg_adapter[s];
+  const int r = a.rank[ad] < 16 * NT ? a.rank[ad] : 16 * NT;
+  const int TM = 16 * MT;
+  const int pos0 = a.seg_start[s] + (tile - a.tile_start[s]) * TM;
+  const int pos_end = a.seg_start[s + 1];
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, row = lane & 15, kg = lane >> 4;
+  const uint16_t* __restrict__ pool = reinterpret_cast<const uint16_t*>(a.pool);
+  const int rpb = (int)(a.block_elems / a.d_in);
+
+  const uint16_t* xp[MT];
+#pragma unroll
+  for (int mt = 0; mt < MT; ++mt) {
+    int pos = pos0 + 16 * mt + row;
+    pos = pos < pos_end ? pos : pos_end - 1;           // padding rows repeat the last token
+    xp[mt] = reinterpret_cast<const uint16_t*>(a.x) + (int64_t)a.perm[pos] * a.ld_x + 8 * kg;
+  }
+  const uint16_t* ap[FLP_MAX_PROJ][NT];
+  bool avalid[NT];
+#pragma unroll
+  for (int nt = 0; nt < NT; ++nt) avalid[nt] = 16 * nt + row < r;
+#pragma unroll
+  for (int p = 0; p < FLP_MAX_PROJ; ++p)
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) {
+      ap[p][nt] = pool;
+      if (p < a.n_proj && r > 0) {
+        const int i = a.proj[p].a_row_base[ad] + (avalid[nt] ? 16 * nt + row : 0);
+        ap[p][nt] = pool + (int64_t)a.tables[a.proj[p].a_tab_off[ad] + i / rpb] * a.block_elems +
+                    (int64_t)(i % rpb) * a.d_in + 8 * kg;
+      }
+    }
+
+  f32x4 acc[MT][FLP_MAX_PROJ][NT];
+#pragma unroll
+  for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+    for (int p = 0; p < FLP_MAX_PROJ; ++p)
+#pragma unroll
+      for (int nt = 0; nt < NT; ++nt) acc[mt][p][nt] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+  const int kbeg = ks * c.k_per_split;
+  const int kend = kbeg + c.k_per_split < a.d_in ? kbeg + c.k_per_split : a.d_in;
+  const u32x4 zero4 = {0u, 0u, 0u, 0u};
+  for (int c0 = kbeg + 32 * wave; c0 < kend; c0 += 128) {
+    vec xf[MT];
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) xf[mt] = vec_from<vec>(*reinterpret_cast<const u32x4*>(xp[mt] + c0));
+#pragma unroll
+    for (int p = 0; p < FLP_MAX_PROJ; ++p) {
+      if (p < a.n_proj) {
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) {
+          if (16 * nt < r) {
+            u32x4 raw = avalid[nt] ? *reinterpret_cast<const u32x4*>(ap[p][nt] + c0) : zero4;
+            vec af = vec_from<vec>(raw);
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt) acc[mt][p][nt] = L::mfma(xf[mt], af, acc[mt][p][nt]);
+          }
+        }
+      }
+    }
+  }
+
+  // ---- sum the four waves' partial tiles in a fixed order, then store
+  const int n_acc = MT * a.n_proj * NT * 4;
+#pragma unroll
+  for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+    for (int p = 0; p < FLP_MAX_PROJ; ++p)
+      if (p < a.n_proj)
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+          for (int i = 0; i < 4; ++i)
+            red[(wave * n_acc + ((mt * a.n_proj + p) * NT + nt) * 4 + i) * 64 + lane] = acc[mt][p][nt][i];
+  __syncthreads();
+  const int RP = 16 * NT;
+  float* __restrict__ vout = a.v + ((int64_t)ks * c.v_rows + (int64_t)tile * TM) * a.n_proj * RP;
+  for (int e = tid; e < n_acc * 64; e += 256) {
+    const float sum = ((red[e] + red[n_acc * 64 + e]) + red[2 * n_acc * 64 + e]) + red[3 * n_acc * 64 + e];
+    const int ln = e & 63, q = e >> 6;
+    const int i = q & 3, nt = (q >> 2) % NT, p = ((q >> 2) / NT) % a.n_proj, mt = (q >> 2) / (NT * a.n_proj);
+    const int trow = 16 * mt + (ln >> 4) * 4 + i, rho = 16 * nt + (ln & 15);
+    vout[((int64_t)trow * a.n_proj + p) * RP + rho] = sum;
+  }
+}
+
+// ------------------------------------------------------------------------------- expand
+template <typename L, int MT, int NT>
+__global__ __launch_bounds__(64) void lora_expand_mfma_kernel(FlpLoraArgs a, FlpLoraMfma c) {
+  typedef typename L::vec vec;
+  typedef typename L::elem elem;
+  typedef typename L::S S;
+  const int tile = blockIdx.x, slab = blockIdx.y, p = blockIdx.z;
+  const int n_seg = *a.n_seg;
+  if (tile >= a.tile_start[n_seg]) return;
+  const flp_lora_proj& pr = a.proj[p];
+  const int col_begin = slab * c.cols_per_slab;
+  if (col_begin >= pr.d_out) return;
+  const int col_end = col_begin + c.cols_per_slab < pr.d_out ? col_begin + c.cols_per_slab : pr.d_out;
+  const int s = find_segment(a.tile_start, n_seg, tile);
+  const int ad = a.seg_adapter[s];
+  const int r = a.rank[ad] < 16 * NT ? a.rank[ad] : 16 * NT;
+  if (r <= 0) return;
+  const float sc = a.scale[ad];
+  const int TM = 16 * MT, RP = 16 * NT;
+  const int pos0 = a.seg_start[s] + (tile - a.tile_start[s]) * TM;
+  const int pos_end = a.seg_start[s + 1];
+  const int lane = threadIdx.x, n = lane & 15, kg = lane >> 4, kq = kg & 1, lo_half = kg >> 1;
+  const uint16_t* __restrict__ pool = reinterpret_cast<const uint16_t*>(a.pool);
+  const int rpb = (int)(a.block_elems / pr.d_out);
+
+  // ---- B operand: this token's scaled v, high part in k-slots 0..15, remainder in 16..31
+  vec vb[MT][NT];
+  uint16_t* yrow[MT];
+  bool tvalid[MT];
+#pragma unroll
+  for (int mt = 0; mt < MT; ++mt) {
+    const int pos = pos0 + 16 * mt + n;
+    tvalid[mt] = pos < pos_end;
+    const int tok = a.perm[tvalid[mt] ? pos : pos_end - 1];
+    yrow[mt] = reinterpret_cast<uint16_t*>(pr.y) + (int64_t)tok * pr.ld_y + 8 * kg;
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) {
+      float v8[8];
+#pragma unroll
+      for (int j = 0; j < 8; ++j) v8[j] = 0.f;
+      if (16 * nt < r) {
+        for (int ks = 0; ks < c.k_splits; ++ks) {
+          const float* vp = a.v + (((int64_t)ks * c.v_rows + (int64_t)tile * TM + 16 * mt + n) * a.n_proj + p) * RP +
+                            16 * nt + 8 * kq;
+          const f32x4 x0 = *reinterpret_cast<const f32x4*>(vp), x1 = *reinterpret_cast<const f32x4*>(vp + 4);
+#pragma unroll
+          for (int j = 0; j < 4; ++j) {
+            v8[j] += x0[j];
+            v8[4 + j] += x1[j];
+          }
+        }
+      }
+      vec out;
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        elem hi, lo;
+        L::split(v8[j] * sc, &hi, &lo);
+        out[j] = lo_half ? lo : hi;
+      }
+      vb[mt][nt] = out;
+    }
+  }
+
+  // ---- A operand rows: B[rho, :] for this lane's 8 ranks of every rank tile
+  const uint16_t* bp[NT][8];
+#pragma unroll
+  for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      const int rho = 16 * nt + 8 * kq + j;
+      const int i = pr.b_row_base[ad] + (rho < r ? rho : 0);
+      bp[nt][j] = pool + (int64_t)a.tables[pr.b_tab_off[ad] + i / rpb] * a.block_elems + (int64_t)(i % rpb) * pr.d_out;
+    }
+
+  const int m = lane & 15;
+  for (int o0 = col_begin; o0 < col_end; o0 += 32) {
+    // column of A-operand row m in column tile tau: o0 + 8*(m/4) + 4*tau + m%4
+    f32x4 acc[MT][2];
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) acc[mt][0] = acc[mt][1] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) {
+      if (16 * nt < r) {
+#pragma unroll
+        for (int tau = 0; tau < 2; ++tau) {
+          const int col = o0 + 8 * (m >> 2) + 4 * tau + (m & 3);
+          uint16_t g8[8];
+#pragma unroll
+          for (int j = 0; j < 8; ++j) g8[j] = (16 * nt + 8 * kq + j < r) ? bp[nt][j][col] : (uint16_t)0;
+          vec af;
+          __builtin_memcpy(&af, g8, 16);
+#pragma unroll
+          for (int mt = 0; mt < MT; ++mt) acc[mt][tau] = L::mfma(af, vb[mt][nt], acc[mt][tau]);
+        }
+      }
+    }
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+      if (tvalid[mt]) {
+        uint16_t ys[8];
+        u32x4 raw = *reinterpret_cast<const u32x4*>(yrow[mt] + o0);
+        __builtin_memcpy(ys, &raw, 16);
+#pragma unroll
+        for (int tau = 0; tau < 2; ++tau)
+#pragma unroll
+          for (int i = 0; i < 4; ++i) ys[4 * tau + i] = S::from_float(S::to_float(ys[4 * tau + i]) + acc[mt][tau][i]);
+        __builtin_memcpy(&raw, ys, 16);
+        *reinterpret_cast<u32x4*>(yrow[mt] + o0) = raw;
+      }
+    }
+  }
+}
+
+template <typename L, int MT, int NT>
+flp_status launch_pair(const FlpLoraArgs& a, const FlpLoraMfma& c, hipStream_t stream) {
+  const size_t smem = (size_t)4 * MT * a.n_proj * NT * 4 * 64 * sizeof(float);
+  static bool attr_set = false;
+  if (!attr_set) {
+    FLP_TRY_HIP(hipFuncSetAttribute((const void*)lora_shrink_mfma_kernel<L, MT, NT>,
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));
+    attr_set = true;
+  }
+  hipLaunchKernelGGL((lora_shrink_mfma_kernel<L, MT, NT>), dim3(c.tiles_bound, c.k_splits), dim3(256), smem, stream, a,
+                     c);
+  FLP_TRY_HIP(hipGetLastError());
+  int max_dout = 0;
+  for (int p = 0; p < a.n_proj; ++p) max_dout = a.proj[p].d_out > max_dout ? a.proj[p].d_out : max_dout;
+  const unsigned slabs = (unsigned)((max_dout + c.cols_per_slab - 1) / c.cols_per_slab);
+  hipLaunchKernelGGL((lora_expand_mfma_kernel<L, MT, NT>), dim3(c.tiles_bound, slabs, a.n_proj), dim3(64), 0, stream,
+                     a, c);
+  FLP_TRY_HIP(hipGetLastError());
+  return FLP_OK;
+}
+
+template <typename L>
+flp_status launch_dtype(const FlpLoraArgs& a, const FlpLoraMfma& c, hipStream_t stream) {
+  const int nt = (a.max_rank + 15) / 16;
+  if (c.mt == 2) {
+    if (nt <= 1) return launch_pair<L, 2, 1>(a, c, stream);
+    if (nt == 2) return launch_pair<L, 2, 2>(a, c, stream);
+    return launch_pair<L, 2, 4>(a, c, stream);
+  }
+  if (nt <= 1) return launch_pair<L, 1, 1>(a, c, stream);
+  if (nt == 2) return launch_pair<L, 1, 2>(a, c, stream);
+  return launch_pair<L, 1, 4>(a, c, stream);
+}
+
+}  // namespace
+
+flp_status flp_launch_lora_mfma(int dtype, const FlpLoraArgs& a, const FlpLoraMfma& c, hipStream_t stream) {
+  if (dtype == FLP_F16) return launch_dtype<LF16>(a, c, stream);
+  if (dtype == FLP_BF16) return launch_dtype<LBF16>(a, c, stream);
+  flp_set_error("LoRA (matrix-core path): dtype %d not supported", dtype);
+  return FLP_ENOTSUP;
+}

@@ -193,7 +193,14 @@ flp_status flp_stage_acquire(flp_pool* p, size_t bytes, FlpStageSlot** out) {
   p->stage_next = (p->stage_next + 1) % kStageSlots;
   if (!s.ev) FLP_TRY_HIP(hipEventCreateWithFlags(&s.ev, hipEventDisableTiming));
   if (s.in_flight) {
-    FLP_TRY_HIP(hipEventSynchronize(s.ev));
+    // normally the slot's last use finished long ago: poll first, block only if it has not
+    hipError_t q = hipEventQuery(s.ev);
+    if (q == hipErrorNotReady) {
+      FLP_TRY_HIP(hipEventSynchronize(s.ev));
+    } else if (q != hipSuccess) {
+      flp_set_error("hipEventQuery failed: %s", hipGetErrorString(q));
+      return FLP_EHIP;
+    }
     s.in_flight = false;
   }
   if (s.cap < bytes) {
@@ -212,8 +219,7 @@ flp_status flp_stage_acquire(flp_pool* p, size_t bytes, FlpStageSlot** out) {
 }
 
 flp_status flp_stage_upload(FlpStageSlot* s, size_t bytes, hipStream_t stream) {
-  if (bytes) FLP_TRY_HIP(hipMemcpyAsync(s->dev, s->host, bytes, hipMemcpyHostToDevice, stream));
-  return FLP_OK;
+  return flp_launch_stage_copy(s->host, s->dev, bytes, stream);   // capacities are multiples of 16
 }
 
 flp_status flp_stage_release(FlpStageSlot* s, hipStream_t stream) {

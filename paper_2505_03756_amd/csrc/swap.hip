@@ -44,7 +44,25 @@ __global__ __launch_bounds__(kThreads) void copy_blocks_kernel(const uint8_t* __
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
+// Small host-to-device copy of staged id / work lists, as a kernel on the caller's stream:
+// it stays in order with the kernels that consume the lists without a hand-off to a copy
+// engine and back.
+__global__ __launch_bounds__(kThreads) void stage_copy_kernel(const u32x4* __restrict__ src, u32x4* __restrict__ dst,
+                                                              int64_t n_vec) {
+  int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+  if (i < n_vec) dst[i] = src[i];
+}
+
 }  // namespace
+
+flp_status flp_launch_stage_copy(const void* src_pinned, void* dst_dev, size_t bytes, hipStream_t stream) {
+  const int64_t n_vec = (int64_t)((bytes + 15) / 16);
+  if (n_vec == 0) return FLP_OK;
+  hipLaunchKernelGGL(stage_copy_kernel, dim3((unsigned)((n_vec + kThreads - 1) / kThreads)), dim3(kThreads), 0, stream,
+                     (const u32x4*)src_pinned, (u32x4*)dst_dev, n_vec);
+  FLP_TRY_HIP(hipGetLastError());
+  return FLP_OK;
+}
 
 flp_status flp_launch_copy_blocks(const uint8_t* src_base, uint8_t* dst_base, const int32_t* src_ids_dev,
                                   const int32_t* dst_ids_dev, int32_t n, int64_t block_bytes, hipStream_t stream) {

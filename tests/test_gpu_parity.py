@@ -122,6 +122,46 @@ def test_lora_matches_oracle(case):
             assert delta > 10 * atol or cfg.dtype == "f32"      # the test would notice a missing delta
 
 
+LORA_CASES = {
+    # T >= 2048 selects the 32-token tiles; rank 16 -> one rank tile; Zipf gives one long segment and a tail
+    "f16_long_segments": lambda: small_cfg("f16", hidden=1024, n_q_heads=8, n_kv_heads=8, n_seqs=24,
+                                           prefix_range=(0, 0), new_range=(40, 180), n_adapters=12, ranks=(16,),
+                                           adapter_dist="zipf", n_dev_blocks=600, swap_in_frac=0.0, seed=82),
+    # ranks 8..64 mixed -> four rank tiles with partially filled ones; many short segments
+    "bf16_mixed_rank": lambda: small_cfg("bf16", hidden=1024, n_q_heads=8, n_kv_heads=8, n_seqs=200,
+                                         prefix_range=(0, 0), new_range=(1, 1), decode_frac=1.0, n_adapters=60,
+                                         ranks=(8, 16, 32, 64), n_dev_blocks=2500, swap_in_frac=0.0, seed=83),
+    # rank 64 with 32-token tiles and a k/v width different from q/o (grouped-query shapes)
+    "f16_rank64_gqa": lambda: small_cfg("f16", hidden=1024, n_q_heads=8, n_kv_heads=2, n_seqs=30,
+                                        prefix_range=(0, 0), new_range=(30, 120), n_adapters=5, ranks=(64,),
+                                        n_dev_blocks=1500, swap_in_frac=0.0, seed=84),
+}
+
+
+@pytest.mark.parametrize("name", list(LORA_CASES))
+def test_lora_matrix_core_shapes(name):
+    cfg = LORA_CASES[name]()
+    step = wl.make_step(cfg)
+    print("\n[lora case %s] T=%d adapters=%d" % (name, step.n_tokens, int((step.rank > 0).sum())), flush=True)
+    dev0 = resident_pool(step)
+    g = GpuStep(step, dev0, np.zeros((1, cfg.block_elems), dev0.dtype))
+    rtol, atol = TOL[cfg.dtype]
+    got = g.lora(["q", "k", "v"])
+    got.update(g.lora(["o"]))
+    for n in ("q", "k", "v", "o"):
+        pr = step.proj[n]
+        want = oracle.lora_apply(dev0, cfg.dtype, step.acts["x"], step.token_adapter, step.rank, step.scale,
+                                 pr.a_tab_off, pr.a_row_base, pr.b_tab_off, pr.b_row_base, step.lora_tables,
+                                 pr.d_out, y_in=step.acts["base_" + n])
+        ok, worst, nbad = close(wl.dequantize(got[n], cfg.dtype), want, rtol, atol)
+        assert ok, "%s: max err %g, %d elements out of tolerance" % (n, worst, nbad)
+        # the delta itself (not just base + delta) must be right: compare it at a tolerance scaled to its size
+        base = wl.dequantize(step.acts["base_" + n], cfg.dtype)
+        ulp = 2.0 ** (-10 if cfg.dtype == "f16" else -7)
+        err = np.abs((wl.dequantize(got[n], cfg.dtype) - base) - (want - base))
+        assert err.max() <= ulp * (np.abs(want).max() + 1.0), (n, err.max())
+
+
 def test_segmentation_bit_exact():
     import torch
     rng = np.random.default_rng(9)
