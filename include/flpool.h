@@ -157,7 +157,9 @@ flp_status flp_paged_prefix_attention(flp_pool* pool, const flp_attn_batch* batc
  * d_out located the same way through b_tab_off / b_row_base.  a = -1 leaves the
  * base term.  A token whose adapter has rank 0 (not resident) is a caller
  * error; its row is left at the base term.  The projections of one batch share
- * x (q, k and v read it once). */
+ * x (q, k and v read it once).  The call keeps its intermediates (segment lists,
+ * fp32 x.A^T) in a workspace owned by the pool: LoRA calls on one pool must be
+ * ordered with respect to each other (same stream, or events between them). */
 #define FLP_MAX_PROJ 4
 
 typedef struct {

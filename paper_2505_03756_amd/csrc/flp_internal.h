@@ -57,6 +57,7 @@ struct flp_pool {
   uint8_t* dev_base = nullptr;
   uint8_t* host_base = nullptr;
   bool own_dev = false, own_host = false;
+  bool host_tier_in_hbm = false;  // the caller placed the "host" tier in device memory
   FlpFreeList tier[2];
   FlpStageSlot stage[kStageSlots];
   int stage_next = 0;
@@ -76,7 +77,7 @@ flp_status flp_workspace(flp_pool* pool, size_t bytes, void** out);
 // ---- kernel launchers (defined in the .hip files) ---------------------------------------
 flp_status flp_launch_copy_blocks(const uint8_t* src_base, uint8_t* dst_base, const int32_t* src_ids_dev,
                                   const int32_t* dst_ids_dev, int32_t n, int64_t block_bytes,
-                                  hipStream_t stream);
+                                  bool over_host_link, hipStream_t stream);
 
 flp_status flp_launch_stage_copy(const void* src_pinned, void* dst_dev, size_t bytes, hipStream_t stream);
 

@@ -109,6 +109,13 @@ extern "C" flp_status flp_pool_create(const flp_pool_config* cfg, flp_pool** out
     }
     p->own_host = true;
   }
+  if (p->host_base && !p->own_host && p->device >= 0) {
+    hipPointerAttribute_t attr{};
+    if (hipPointerGetAttributes(&attr, p->host_base) == hipSuccess)
+      p->host_tier_in_hbm = attr.type == hipMemoryTypeDevice;
+    else
+      (void)hipGetLastError();
+  }
   freelist_init(p->tier[0], cfg->n_dev_blocks);
   freelist_init(p->tier[1], cfg->n_host_blocks);
   *out = p;
@@ -204,7 +211,9 @@ flp_status flp_stage_acquire(flp_pool* p, size_t bytes, FlpStageSlot** out) {
     s.in_flight = false;
   }
   if (s.cap < bytes) {
-    size_t cap = 1 << 16;
+    // freeing device or pinned memory waits for the whole device, so a slot starts large
+    // enough (1 MiB) that ordinary id lists and work lists never make it grow
+    size_t cap = 1 << 20;
     while (cap < bytes) cap <<= 1;
     if (s.host) FLP_TRY_HIP(hipHostFree(s.host));
     if (s.dev) FLP_TRY_HIP(hipFree(s.dev));
@@ -281,7 +290,7 @@ static flp_status swap_common(flp_pool* p, int32_t n, const int32_t* src_ids, co
   const uint8_t* src_base = src_tier == 0 ? p->dev_base : p->host_base;
   uint8_t* dst_base = dst_tier == 0 ? p->dev_base : p->host_base;
   const int32_t* d = (const int32_t*)slot->dev;
-  flp_status st = flp_launch_copy_blocks(src_base, dst_base, d, d + n, n, p->block_bytes, stream);
+  flp_status st = flp_launch_copy_blocks(src_base, dst_base, d, d + n, n, p->block_bytes, !p->host_tier_in_hbm, stream);
   flp_status st2 = flp_stage_release(slot, stream);
   return st != FLP_OK ? st : st2;
 }

@@ -6,6 +6,8 @@
 // transfer itself rather than one copy-engine submission per block.
 #include <hip/hip_runtime.h>
 
+#include <cstdlib>
+
 #include "flp_internal.h"
 
 namespace {
@@ -13,31 +15,37 @@ namespace {
 constexpr int kThreads = 256;
 constexpr int kUnroll = 4;
 
+// A fixed number of workgroups walks the (block, chunk) grid with a stride: the host link
+// needs only a few hundred KiB in flight to stay busy, so a small resident grid reaches the
+// same rate as one workgroup per chunk and leaves the rest of the chip to the compute
+// kernels that run beside the swap on another stream.
 template <typename V>
 __global__ __launch_bounds__(kThreads) void copy_blocks_kernel(const uint8_t* __restrict__ src_base,
                                                                uint8_t* __restrict__ dst_base,
                                                                const int32_t* __restrict__ src_ids,
                                                                const int32_t* __restrict__ dst_ids,
                                                                int64_t block_bytes, int32_t chunks_per_block,
-                                                               int64_t vec_per_chunk) {
-  const int32_t blk = blockIdx.x / chunks_per_block;
-  const int32_t chunk = blockIdx.x - blk * chunks_per_block;
-  const V* __restrict__ s = reinterpret_cast<const V*>(src_base + (int64_t)src_ids[blk] * block_bytes);
-  V* __restrict__ d = reinterpret_cast<V*>(dst_base + (int64_t)dst_ids[blk] * block_bytes);
+                                                               int64_t vec_per_chunk, int64_t total_chunks) {
   const int64_t nvec = block_bytes / (int64_t)sizeof(V);
-  const int64_t lo = (int64_t)chunk * vec_per_chunk;
-  const int64_t hi = lo + vec_per_chunk < nvec ? lo + vec_per_chunk : nvec;
-  for (int64_t i = lo + threadIdx.x; i < hi; i += kThreads * kUnroll) {
-    V r[kUnroll];
+  for (int64_t w = blockIdx.x; w < total_chunks; w += gridDim.x) {
+    const int32_t blk = (int32_t)(w / chunks_per_block);
+    const int32_t chunk = (int32_t)(w - (int64_t)blk * chunks_per_block);
+    const V* __restrict__ s = reinterpret_cast<const V*>(src_base + (int64_t)src_ids[blk] * block_bytes);
+    V* __restrict__ d = reinterpret_cast<V*>(dst_base + (int64_t)dst_ids[blk] * block_bytes);
+    const int64_t lo = (int64_t)chunk * vec_per_chunk;
+    const int64_t hi = lo + vec_per_chunk < nvec ? lo + vec_per_chunk : nvec;
+    for (int64_t i = lo + threadIdx.x; i < hi; i += kThreads * kUnroll) {
+      V r[kUnroll];
 #pragma unroll
-    for (int u = 0; u < kUnroll; ++u) {
-      int64_t j = i + (int64_t)u * kThreads;
-      if (j < hi) r[u] = __builtin_nontemporal_load(s + j);
-    }
+      for (int u = 0; u < kUnroll; ++u) {
+        int64_t j = i + (int64_t)u * kThreads;
+        if (j < hi) r[u] = __builtin_nontemporal_load(s + j);
+      }
 #pragma unroll
-    for (int u = 0; u < kUnroll; ++u) {
-      int64_t j = i + (int64_t)u * kThreads;
-      if (j < hi) __builtin_nontemporal_store(r[u], d + j);
+      for (int u = 0; u < kUnroll; ++u) {
+        int64_t j = i + (int64_t)u * kThreads;
+        if (j < hi) __builtin_nontemporal_store(r[u], d + j);
+      }
     }
   }
 }
@@ -65,24 +73,28 @@ flp_status flp_launch_stage_copy(const void* src_pinned, void* dst_dev, size_t b
 }
 
 flp_status flp_launch_copy_blocks(const uint8_t* src_base, uint8_t* dst_base, const int32_t* src_ids_dev,
-                                  const int32_t* dst_ids_dev, int32_t n, int64_t block_bytes, hipStream_t stream) {
+                                  const int32_t* dst_ids_dev, int32_t n, int64_t block_bytes, bool over_host_link,
+                                  hipStream_t stream) {
   if (n <= 0) return FLP_OK;
   const int64_t chunk_bytes = 16384;
-  int64_t chunks = (block_bytes + chunk_bytes - 1) / chunk_bytes;
-  if ((int64_t)n * chunks > 0x7fffffffLL) {
-    flp_set_error("swap: list of %d blocks is too long for one launch", n);
-    return FLP_ERANGE;
-  }
-  dim3 grid((unsigned)((int64_t)n * chunks));
+  const int64_t chunks = (block_bytes + chunk_bytes - 1) / chunk_bytes;
+  const int64_t total = (int64_t)n * chunks;
+  // measured on MI355X: 16 resident workgroups already saturate the host link (57 GB/s in,
+  // 55 GB/s out), and every further workgroup that waits on host-link reads slows the HBM
+  // traffic of the kernels running beside the swap (96 workgroups: a streaming copy on another
+  // stream runs 4x slower; 16: 1.1x); a tier that lives in device memory wants the whole chip
+  static const int tune = [] { const char* e = getenv("FLP_SWAP_WGS"); return e ? atoi(e) : 0; }();
+  const int64_t max_wgs = tune > 0 ? tune : (over_host_link ? 16 : 2048);
+  dim3 grid((unsigned)(total < max_wgs ? total : max_wgs));
   if (block_bytes % 16 == 0) {
     hipLaunchKernelGGL(copy_blocks_kernel<u32x4>, grid, dim3(kThreads), 0, stream, src_base, dst_base, src_ids_dev,
-                       dst_ids_dev, block_bytes, (int32_t)chunks, chunk_bytes / 16);
+                       dst_ids_dev, block_bytes, (int32_t)chunks, chunk_bytes / 16, total);
   } else if (block_bytes % 4 == 0) {
     hipLaunchKernelGGL(copy_blocks_kernel<uint32_t>, grid, dim3(kThreads), 0, stream, src_base, dst_base,
-                       src_ids_dev, dst_ids_dev, block_bytes, (int32_t)chunks, chunk_bytes / 4);
+                       src_ids_dev, dst_ids_dev, block_bytes, (int32_t)chunks, chunk_bytes / 4, total);
   } else {
     hipLaunchKernelGGL(copy_blocks_kernel<uint16_t>, grid, dim3(kThreads), 0, stream, src_base, dst_base,
-                       src_ids_dev, dst_ids_dev, block_bytes, (int32_t)chunks, chunk_bytes / 2);
+                       src_ids_dev, dst_ids_dev, block_bytes, (int32_t)chunks, chunk_bytes / 2, total);
   }
   FLP_TRY_HIP(hipGetLastError());
   return FLP_OK;

@@ -8,16 +8,20 @@ def poison_value(dtype):
     return np.float32(np.nan) if dtype == "f32" else (0x7E00 if dtype == "f16" else 0x7FC0)
 
 
-def build_pools(step, poison_rest=False):
+def build_pools(step, poison_rest=False, into=None):
     """Device-tier and host-tier pool images ([n_blocks, block_elems] storage arrays) at
     the start of the step: blocks on the swap-in list have their content on the host tier
-    and poison on the device tier."""
+    and poison on the device tier.  `into=(dev, host)` adds the step to existing images
+    (several steps with disjoint blocks in one pool)."""
     cfg = step.cfg
     sd = wl.storage_dtype(cfg.dtype)
-    dev = np.zeros((cfg.n_dev_blocks, cfg.block_elems), dtype=sd)
-    host = np.zeros((cfg.n_host_blocks, cfg.block_elems), dtype=sd)
-    if poison_rest:
-        dev[:] = poison_value(cfg.dtype)
+    if into is None:
+        dev = np.zeros((cfg.n_dev_blocks, cfg.block_elems), dtype=sd)
+        host = np.zeros((cfg.n_host_blocks, cfg.block_elems), dtype=sd)
+        if poison_rest:
+            dev[:] = poison_value(cfg.dtype)
+    else:
+        dev, host = into
     dev[step.content_ids] = step.content
     if len(step.swap_in_dev):
         host[step.swap_in_host] = dev[step.swap_in_dev]
@@ -60,19 +64,28 @@ def to_np(t, like_dtype):
     return a.view(np.uint16) if like_dtype == np.uint16 else a
 
 
-class GpuStep:
-    """Uploads a synthetic Step and owns the flpool handle over torch-allocated tiers."""
+class GpuPool:
+    """The two tiers as torch tensors (device memory / pinned host memory) plus the flpool handle."""
 
-    def __init__(self, step, dev_img, host_img):
-        import torch
+    def __init__(self, cfg, dev_img, host_img):
         from paper_2505_03756_amd import flpool
-        cfg = step.cfg
-        self.step, self.cfg = step, cfg
+        self.cfg = cfg
         self.sd = wl.storage_dtype(cfg.dtype)
         self.dev = to_dev(dev_img)
         self.host = to_dev(host_img, pin=True)
         self.pool = flpool.Pool(cfg.dtype, cfg.n_kv_heads, cfg.head_dim, dev_img.shape[0], host_img.shape[0],
                                 block_tokens=cfg.block_tokens, dev=self.dev, host=self.host)
+
+
+class GpuStep:
+    """Uploads a synthetic Step; owns (or shares) the pool it runs on."""
+
+    def __init__(self, step, dev_img=None, host_img=None, gpool=None):
+        import torch
+        cfg = step.cfg
+        self.step, self.cfg = step, cfg
+        self.gpool = gpool if gpool is not None else GpuPool(cfg, dev_img, host_img)
+        self.sd, self.dev, self.host, self.pool = self.gpool.sd, self.gpool.dev, self.gpool.host, self.gpool.pool
         self.kv_tables = to_dev(step.kv_tables)
         self.lora_tables = to_dev(step.lora_tables)
         self.token_adapter = to_dev(step.token_adapter)
