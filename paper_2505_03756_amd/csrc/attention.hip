@@ -20,39 +20,58 @@ namespace {
 constexpr int BT = 16;   // token positions per block
 
 // ------------------------------------------------------------------------------- append
-// One workgroup per (sequence, block) unit: copies the K rows of the unit's slots and
-// writes the V columns transposed, a full 16-slot run per (head, channel) when the unit
-// covers the whole block.
+// One workgroup per (sequence, block, 256 vector-columns) unit.  A thread owns 16 bytes of a
+// token row (8 channels of one head, or 4 for fp32): it copies them into the K rows of the
+// unit's slots and, for V, gathers the unit's slots into registers and writes each channel's
+// 16-slot run with 16-byte stores when the unit covers the whole block.
 template <typename S, int D>
 __global__ __launch_bounds__(256) void kv_append_kernel(FlpAttnArgs a, const FlpAppendUnit* __restrict__ units) {
+  constexpr int EPV = 16 / (int)sizeof(S);          // elements per 16-byte vector
+  constexpr int VPR = BT / EPV;                     // vectors per 16-slot V run
   const FlpAppendUnit u = units[blockIdx.x];
+  const int row = a.n_kv * D;                       // elements per token in k_new / v_new
+  const int e0 = (blockIdx.y * 256 + threadIdx.x) * EPV;
+  if (e0 >= row) return;
   const int64_t blk = a.tables[(int64_t)u.seq * a.max_blocks + u.blk_idx];
   S* __restrict__ base = reinterpret_cast<S*>(a.pool) + blk * a.block_elems;
-  const S* __restrict__ kn = reinterpret_cast<const S*>(a.k_new);
-  const S* __restrict__ vn = reinterpret_cast<const S*>(a.v_new);
-  const int row = a.n_kv * D;          // elements per token in k_new / v_new
+  const S* __restrict__ kn = reinterpret_cast<const S*>(a.k_new) + (int64_t)u.t_first * row + e0;
+  const S* __restrict__ vn = reinterpret_cast<const S*>(a.v_new) + (int64_t)u.t_first * row + e0;
+  const int g = e0 / D, c0 = e0 - g * D;
   const int ns = u.s1 - u.s0;
-  // K: rows of D contiguous elements
-  for (int idx = threadIdx.x; idx < ns * row; idx += 256) {
-    int s = idx / row, e = idx - s * row;
-    int g = e / D, c = e - g * D;
-    base[((int64_t)g * BT + (u.s0 + s)) * D + c] = kn[(int64_t)(u.t_first + s) * row + e];
-  }
-  // V: element e = (g, c) of each slot goes to ((g*D + c)*16 + slot)
-  S* __restrict__ vbase = base + (int64_t)a.n_kv * BT * D;
-  for (int e = threadIdx.x; e < row; e += 256) {
-    S* dst = vbase + (int64_t)e * BT;   // (g*D + c) == e
-    if (ns == BT) {
-      S vals[BT];
+  S* __restrict__ kdst = base + ((int64_t)g * BT + u.s0) * D + c0;
+  S* __restrict__ vdst = base + (int64_t)a.n_kv * BT * D + ((int64_t)g * D + c0) * BT;
+  if (ns == BT) {
+    u32x4 vv[BT];
 #pragma unroll
-      for (int s = 0; s < BT; ++s) vals[s] = vn[(int64_t)(u.t_first + s) * row + e];
-      constexpr int NV = BT * (int)sizeof(S) / 16;
-      u32x4 packed[NV];
-      __builtin_memcpy(packed, vals, sizeof(vals));
+    for (int s = 0; s < BT; ++s) vv[s] = *reinterpret_cast<const u32x4*>(vn + (int64_t)s * row);
 #pragma unroll
-      for (int v = 0; v < NV; ++v) reinterpret_cast<u32x4*>(dst)[v] = packed[v];
-    } else {
-      for (int s = 0; s < ns; ++s) dst[u.s0 + s] = vn[(int64_t)(u.t_first + s) * row + e];
+    for (int h = 0; h < 2; ++h) {                   // K in two halves to keep the register count down
+      u32x4 kv[BT / 2];
+#pragma unroll
+      for (int s = 0; s < BT / 2; ++s) kv[s] = *reinterpret_cast<const u32x4*>(kn + (int64_t)(h * (BT / 2) + s) * row);
+#pragma unroll
+      for (int s = 0; s < BT / 2; ++s) *reinterpret_cast<u32x4*>(kdst + (h * (BT / 2) + s) * D) = kv[s];
+    }
+    S vals[BT][EPV];
+    __builtin_memcpy(vals, vv, sizeof(vals));
+#pragma unroll
+    for (int c = 0; c < EPV; ++c) {
+      S run[BT];
+#pragma unroll
+      for (int s = 0; s < BT; ++s) run[s] = vals[s][c];
+      u32x4 packed[VPR];
+      __builtin_memcpy(packed, run, sizeof(run));
+#pragma unroll
+      for (int v = 0; v < VPR; ++v) reinterpret_cast<u32x4*>(vdst + c * BT)[v] = packed[v];
+    }
+  } else {
+    for (int s = 0; s < ns; ++s) {
+      *reinterpret_cast<u32x4*>(kdst + s * D) = *reinterpret_cast<const u32x4*>(kn + (int64_t)s * row);
+      S vals[EPV];
+      u32x4 raw = *reinterpret_cast<const u32x4*>(vn + (int64_t)s * row);
+      __builtin_memcpy(vals, &raw, 16);
+#pragma unroll
+      for (int c = 0; c < EPV; ++c) vdst[c * BT + u.s0 + s] = vals[c];
     }
   }
 }
@@ -200,14 +219,16 @@ flp_status flp_launch_kv_append(int dtype, int head_dim, const FlpAttnArgs& a, c
                                 int32_t n_units, hipStream_t stream) {
   if (n_units <= 0) return FLP_OK;
   // the append kernel only moves storage words: fp16 and bf16 share the 16-bit instance
+  const int epv = dtype == FLP_F32 ? 4 : 8;
+  dim3 grid((unsigned)n_units, (unsigned)((a.n_kv * head_dim + 256 * epv - 1) / (256 * epv)));
   if (dtype == FLP_F32 && head_dim == 64)
-    hipLaunchKernelGGL((kv_append_kernel<float, 64>), dim3(n_units), dim3(256), 0, stream, a, units_dev);
+    hipLaunchKernelGGL((kv_append_kernel<float, 64>), grid, dim3(256), 0, stream, a, units_dev);
   else if (dtype == FLP_F32 && head_dim == 128)
-    hipLaunchKernelGGL((kv_append_kernel<float, 128>), dim3(n_units), dim3(256), 0, stream, a, units_dev);
+    hipLaunchKernelGGL((kv_append_kernel<float, 128>), grid, dim3(256), 0, stream, a, units_dev);
   else if (dtype != FLP_F32 && head_dim == 64)
-    hipLaunchKernelGGL((kv_append_kernel<uint16_t, 64>), dim3(n_units), dim3(256), 0, stream, a, units_dev);
+    hipLaunchKernelGGL((kv_append_kernel<uint16_t, 64>), grid, dim3(256), 0, stream, a, units_dev);
   else if (dtype != FLP_F32 && head_dim == 128)
-    hipLaunchKernelGGL((kv_append_kernel<uint16_t, 128>), dim3(n_units), dim3(256), 0, stream, a, units_dev);
+    hipLaunchKernelGGL((kv_append_kernel<uint16_t, 128>), grid, dim3(256), 0, stream, a, units_dev);
   else {
     flp_set_error("kv_append: head_dim %d not supported", head_dim);
     return FLP_ENOTSUP;

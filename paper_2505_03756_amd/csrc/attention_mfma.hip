@@ -190,18 +190,33 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(FlpAttnArgs a, const 
 #pragma unroll
           for (int i = 0; i < 16; ++i) S[st][nt][i] = 0.f;
       const uint8_t* krowp = buf + krow * 256;
+      // K fragments are fetched from LDS one contraction step ahead of the MFMAs that use
+      // them, so the LDS latency hides behind the previous step's two instructions
+      vec ka[2][2];
+      ka[0][0] = as_vec<vec>(*reinterpret_cast<const u32x4*>(krowp + ((hf ^ a_swz) << 4)));
+      ka[0][1] = as_vec<vec>(*reinterpret_cast<const u32x4*>(krowp + 32 * 256 + ((hf ^ a_swz) << 4)));
 #pragma unroll
       for (int kk = 0; kk < 8; ++kk) {
-        const int coff = ((2 * kk + hf) ^ a_swz) << 4;
+        if (kk + 1 < 8) {
+          const int coff = ((2 * (kk + 1) + hf) ^ a_swz) << 4;
+          ka[(kk + 1) & 1][0] = as_vec<vec>(*reinterpret_cast<const u32x4*>(krowp + coff));
+          ka[(kk + 1) & 1][1] = as_vec<vec>(*reinterpret_cast<const u32x4*>(krowp + 32 * 256 + coff));
+        }
         // the two sub-tiles are independent accumulation chains: alternate them
-        vec ka0 = as_vec<vec>(*reinterpret_cast<const u32x4*>(krowp + coff));
-        vec ka1 = as_vec<vec>(*reinterpret_cast<const u32x4*>(krowp + 32 * 256 + coff));
 #pragma unroll
         for (int nt = 0; nt < NRT; ++nt) {
-          S[0][nt] = M::mfma(ka0, qf[nt][kk], S[0][nt]);
-          S[1][nt] = M::mfma(ka1, qf[nt][kk], S[1][nt]);
+          S[0][nt] = M::mfma(ka[kk & 1][0], qf[nt][kk], S[0][nt]);
+          S[1][nt] = M::mfma(ka[kk & 1][1], qf[nt][kk], S[1][nt]);
         }
       }
+      // pin that order for the instruction scheduler: 4 LDS reads, then (2 MFMA, 2 LDS reads) x 7, 2 MFMA
+      __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
+#pragma unroll
+      for (int kk = 0; kk < 7; ++kk) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 2 * NRT, 0);
+        __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+      }
+      __builtin_amdgcn_sched_group_barrier(0x008, 2 * NRT, 0);
       // ---- causal mask on the tiles that reach past the first row's position
       if (BN * kt + BN - 1 > wave_min_pos) {
 #pragma unroll

@@ -37,9 +37,25 @@ __global__ __launch_bounds__(1024) void lora_segment_kernel(int32_t T, const int
   const int chunk = (((T + kSegWaves - 1) / kSegWaves) + 63) & ~63;
   const int lo = wave * chunk < T ? wave * chunk : T;
   const int hi = lo + chunk < T ? lo + chunk : T;
-  for (int t = lo + lane; t < hi; t += 64) {
-    int a = token_adapter[t];
-    if (a >= 0 && a < n_ad) atomicAdd(&whist[wave * n_ad + a], 1);
+  // counting: the lanes that hold the same adapter are matched with ballots and their leader
+  // adds the group's size (tokens of one sequence share an adapter, so a wave usually sees
+  // one or two distinct ids per 64 tokens; no atomics, each wave owns its row of counters)
+  {
+    volatile int32_t* cnt_row = whist + wave * n_ad;
+    for (int t0 = lo; t0 < hi; t0 += 64) {
+      const int t = t0 + lane;
+      const int a = t < hi ? token_adapter[t] : -1;
+      const bool valid = a >= 0 && a < n_ad;
+      uint64_t remaining = __ballot(valid);
+      while (remaining) {
+        const int leader = __ffsll((long long)remaining) - 1;
+        const int v = __shfl(a, leader);
+        const uint64_t same = __ballot(valid && a == v);
+        if (lane == leader) cnt_row[v] = cnt_row[v] + __popcll(same);
+        __builtin_amdgcn_wave_barrier();
+        remaining &= ~same;
+      }
+    }
   }
   __syncthreads();
 
