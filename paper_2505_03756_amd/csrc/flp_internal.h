@@ -134,6 +134,7 @@ struct FlpLoraArgs {
   int32_t* seg_start;
   int32_t* perm;
   int32_t* tile_start;         // [n_seg + 1] first tile of each segment (matrix-core kernels)
+  int32_t* group_start;        // [n_seg + 1] first tile group of each segment (expand kernel)
 };
 
 struct FlpLoraMfma {
@@ -142,10 +143,12 @@ struct FlpLoraMfma {
   int32_t v_rows;              // rows of one split's partial v buffer (= tiles_bound * 16 * mt)
   int32_t cols_per_slab;
   int32_t tiles_bound;         // host-side upper bound of the number of tiles
+  int32_t group_tokens;        // tokens per tile group of the expand kernel (multiple of 16*mt)
+  int32_t groups_bound;
 };
 
 flp_status flp_launch_lora_segment(int32_t T, const int32_t* token_adapter, int32_t n_adapters, int32_t* n_seg,
                                    int32_t* seg_adapter, int32_t* seg_start, int32_t* perm, int32_t tm,
-                                   int32_t* tile_start, hipStream_t stream);
+                                   int32_t* tile_start, int32_t tg, int32_t* group_start, hipStream_t stream);
 flp_status flp_launch_lora_mfma(int dtype, const FlpLoraArgs& a, const FlpLoraMfma& c, hipStream_t stream);
 flp_status flp_launch_lora_simple(int dtype, const FlpLoraArgs& a, hipStream_t stream);

@@ -23,12 +23,13 @@ __global__ __launch_bounds__(1024) void lora_segment_kernel(int32_t T, const int
                                                             int32_t* __restrict__ seg_adapter,
                                                             int32_t* __restrict__ seg_start,
                                                             int32_t* __restrict__ perm, int32_t tm,
-                                                            int32_t* __restrict__ tile_start) {
+                                                            int32_t* __restrict__ tile_start, int32_t tg,
+                                                            int32_t* __restrict__ group_start) {
   extern __shared__ int32_t sm[];
   int32_t* whist = sm;                         // [kSegWaves][n_ad]: counts, then running cursors
   int32_t* tot = sm + kSegWaves * n_ad;        // [n_ad] tokens per adapter
   int32_t* seg_off = tot + n_ad;               // [n_ad] first output position of the adapter
-  int32_t* wsum = seg_off + n_ad;              // [3*kSegWaves + 3] scan scratch
+  int32_t* wsum = seg_off + n_ad;              // [4*kSegWaves + 4] scan scratch
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
 
   for (int i = tid; i < kSegWaves * n_ad; i += 1024) whist[i] = 0;
@@ -73,52 +74,60 @@ __global__ __launch_bounds__(1024) void lora_segment_kernel(int32_t T, const int
 
   // exclusive scan over adapters of (count, non-empty flag); thread i owns a run of adapters
   const int per = (n_ad + 1023) / 1024;
-  // (a third quantity rides along: the number of tm-token tiles, for the matrix-core kernels)
-  int cnt = 0, flg = 0, til = 0;
+  // (two more quantities ride along for the matrix-core kernels: the number of tm-token tiles
+  // and the number of tg-token tile groups)
+  int cnt = 0, flg = 0, til = 0, grp = 0;
   for (int k = 0; k < per; ++k) {
     int a = tid * per + k;
     if (a < n_ad) {
       cnt += tot[a];
       flg += tot[a] > 0;
       if (tm > 0) til += (tot[a] + tm - 1) / tm;
+      if (tg > 0) grp += (tot[a] + tg - 1) / tg;
     }
   }
-  int icnt = cnt, iflg = flg, itil = til;      // inclusive wave scan
+  int icnt = cnt, iflg = flg, itil = til, igrp = grp;      // inclusive wave scan
 #pragma unroll
   for (int off = 1; off < 64; off <<= 1) {
-    int c = __shfl_up(icnt, off), f = __shfl_up(iflg, off), t = __shfl_up(itil, off);
+    int c = __shfl_up(icnt, off), f = __shfl_up(iflg, off), t = __shfl_up(itil, off), gq = __shfl_up(igrp, off);
     if (lane >= off) {
       icnt += c;
       iflg += f;
       itil += t;
+      igrp += gq;
     }
   }
   if (lane == 63) {
     wsum[wave] = icnt;
     wsum[kSegWaves + wave] = iflg;
     wsum[2 * kSegWaves + wave] = itil;
+    wsum[3 * kSegWaves + wave] = igrp;
   }
   __syncthreads();
   if (tid == 0) {
-    int rc = 0, rf = 0, rt = 0;
+    int rc = 0, rf = 0, rt = 0, rg = 0;
     for (int w = 0; w < kSegWaves; ++w) {
-      int c = wsum[w], f = wsum[kSegWaves + w], t = wsum[2 * kSegWaves + w];
+      int c = wsum[w], f = wsum[kSegWaves + w], t = wsum[2 * kSegWaves + w], gq = wsum[3 * kSegWaves + w];
       wsum[w] = rc;
       wsum[kSegWaves + w] = rf;
       wsum[2 * kSegWaves + w] = rt;
+      wsum[3 * kSegWaves + w] = rg;
       rc += c;
       rf += f;
       rt += t;
+      rg += gq;
     }
-    wsum[3 * kSegWaves] = rc;
-    wsum[3 * kSegWaves + 1] = rf;
-    wsum[3 * kSegWaves + 2] = rt;
+    wsum[4 * kSegWaves] = rc;
+    wsum[4 * kSegWaves + 1] = rf;
+    wsum[4 * kSegWaves + 2] = rt;
+    wsum[4 * kSegWaves + 3] = rg;
   }
   __syncthreads();
   {
     int pos = wsum[wave] + icnt - cnt;         // tokens before this thread's first adapter
     int seg = wsum[kSegWaves + wave] + iflg - flg;
     int tl = wsum[2 * kSegWaves + wave] + itil - til;
+    int gr = wsum[3 * kSegWaves + wave] + igrp - grp;
     for (int k = 0; k < per; ++k) {
       int a = tid * per + k;
       if (a < n_ad) {
@@ -127,16 +136,19 @@ __global__ __launch_bounds__(1024) void lora_segment_kernel(int32_t T, const int
           seg_adapter[seg] = a;
           seg_start[seg] = pos;
           if (tile_start) tile_start[seg] = tl;
+          if (group_start) group_start[seg] = gr;
           ++seg;
         }
         pos += tot[a];
         if (tm > 0) tl += (tot[a] + tm - 1) / tm;
+        if (tg > 0) gr += (tot[a] + tg - 1) / tg;
       }
     }
     if (tid == 0) {
-      *n_seg = wsum[3 * kSegWaves + 1];
-      seg_start[wsum[3 * kSegWaves + 1]] = wsum[3 * kSegWaves];
-      if (tile_start) tile_start[wsum[3 * kSegWaves + 1]] = wsum[3 * kSegWaves + 2];
+      *n_seg = wsum[4 * kSegWaves + 1];
+      seg_start[wsum[4 * kSegWaves + 1]] = wsum[4 * kSegWaves];
+      if (tile_start) tile_start[wsum[4 * kSegWaves + 1]] = wsum[4 * kSegWaves + 2];
+      if (group_start) group_start[wsum[4 * kSegWaves + 1]] = wsum[4 * kSegWaves + 3];
     }
   }
   __syncthreads();
@@ -264,8 +276,8 @@ __global__ __launch_bounds__(256) void lora_expand_rows_kernel(FlpLoraArgs a) {
 
 flp_status flp_launch_lora_segment(int32_t T, const int32_t* token_adapter, int32_t n_adapters, int32_t* n_seg,
                                    int32_t* seg_adapter, int32_t* seg_start, int32_t* perm, int32_t tm,
-                                   int32_t* tile_start, hipStream_t stream) {
-  const size_t smem = ((size_t)(kSegWaves + 2) * (size_t)(n_adapters > 0 ? n_adapters : 1) + 3 * kSegWaves + 3) * 4;
+                                   int32_t* tile_start, int32_t tg, int32_t* group_start, hipStream_t stream) {
+  const size_t smem = ((size_t)(kSegWaves + 2) * (size_t)(n_adapters > 0 ? n_adapters : 1) + 4 * kSegWaves + 4) * 4;
   static bool attr_set = false;
   if (!attr_set) {
     FLP_TRY_HIP(hipFuncSetAttribute((const void*)lora_segment_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -273,7 +285,7 @@ flp_status flp_launch_lora_segment(int32_t T, const int32_t* token_adapter, int3
     attr_set = true;
   }
   hipLaunchKernelGGL(lora_segment_kernel, dim3(1), dim3(1024), smem, stream, T, token_adapter, n_adapters, n_seg,
-                     seg_adapter, seg_start, perm, tm, tile_start);
+                     seg_adapter, seg_start, perm, tm, tile_start, tg, group_start);
   FLP_TRY_HIP(hipGetLastError());
   return FLP_OK;
 }

@@ -168,113 +168,134 @@ __global__ __launch_bounds__(256) void lora_shrink_mfma_kernel(FlpLoraArgs a, Fl
 }
 
 // ------------------------------------------------------------------------------- expand
-template <typename L, int MT, int NT>
+// One wave per (tile group, column slab, projection).  The slab's B coefficients are gathered
+// once into MFMA A-operand fragments that stay in registers (64 VGPRs) while the wave walks
+// the group's 16-token sub-tiles, so the 2-byte gathers are amortised over up to 256 tokens
+// and the inner loop is the y stream: 16-byte read, two MFMAs per rank tile, 16-byte write.
+template <typename L, int NT>
 __global__ __launch_bounds__(64) void lora_expand_mfma_kernel(FlpLoraArgs a, FlpLoraMfma c) {
   typedef typename L::vec vec;
   typedef typename L::elem elem;
   typedef typename L::S S;
-  const int tile = blockIdx.x, slab = blockIdx.y, p = blockIdx.z;
+  constexpr int CH = 8 / NT;                          // 32-column chunks per slab
+  const int group = blockIdx.x, slab = blockIdx.y, p = blockIdx.z;
   const int n_seg = *a.n_seg;
-  if (tile >= a.tile_start[n_seg]) return;
+  if (group >= a.group_start[n_seg]) return;
   const flp_lora_proj& pr = a.proj[p];
-  const int col_begin = slab * c.cols_per_slab;
-  if (col_begin >= pr.d_out) return;
-  const int col_end = col_begin + c.cols_per_slab < pr.d_out ? col_begin + c.cols_per_slab : pr.d_out;
-  const int s = find_segment(a.tile_start, n_seg, tile);
+  const int slab_begin = slab * c.cols_per_slab;
+  if (slab_begin >= pr.d_out) return;
+  const int s = find_segment(a.group_start, n_seg, group);
   const int ad = a.seg_adapter[s];
   const int r = a.rank[ad] < 16 * NT ? a.rank[ad] : 16 * NT;
   if (r <= 0) return;
   const float sc = a.scale[ad];
-  const int TM = 16 * MT, RP = 16 * NT;
-  const int pos0 = a.seg_start[s] + (tile - a.tile_start[s]) * TM;
+  const int RP = 16 * NT, TM = 16 * c.mt;
+  const int off0 = (group - a.group_start[s]) * c.group_tokens;       // first token of the group inside its segment
+  const int pos0 = a.seg_start[s] + off0;
   const int pos_end = a.seg_start[s + 1];
-  const int lane = threadIdx.x, n = lane & 15, kg = lane >> 4, kq = kg & 1, lo_half = kg >> 1;
+  const int pos_stop = pos0 + c.group_tokens < pos_end ? pos0 + c.group_tokens : pos_end;
+  const int64_t vrow0 = (int64_t)a.tile_start[s] * TM + off0;         // the segment's rows of v are contiguous
+  const int lane = threadIdx.x, n = lane & 15, kg = lane >> 4, kq = kg & 1, lo_half = kg >> 1, m = lane & 15;
   const uint16_t* __restrict__ pool = reinterpret_cast<const uint16_t*>(a.pool);
   const int rpb = (int)(a.block_elems / pr.d_out);
 
-  // ---- B operand: this token's scaled v, high part in k-slots 0..15, remainder in 16..31
-  vec vb[MT][NT];
-  uint16_t* yrow[MT];
-  bool tvalid[MT];
-#pragma unroll
-  for (int mt = 0; mt < MT; ++mt) {
-    const int pos = pos0 + 16 * mt + n;
-    tvalid[mt] = pos < pos_end;
-    const int tok = a.perm[tvalid[mt] ? pos : pos_end - 1];
-    yrow[mt] = reinterpret_cast<uint16_t*>(pr.y) + (int64_t)tok * pr.ld_y + 8 * kg;
-#pragma unroll
-    for (int nt = 0; nt < NT; ++nt) {
-      float v8[8];
-#pragma unroll
-      for (int j = 0; j < 8; ++j) v8[j] = 0.f;
-      if (16 * nt < r) {
-        for (int ks = 0; ks < c.k_splits; ++ks) {
-          const float* vp = a.v + (((int64_t)ks * c.v_rows + (int64_t)tile * TM + 16 * mt + n) * a.n_proj + p) * RP +
-                            16 * nt + 8 * kq;
-          const f32x4 x0 = *reinterpret_cast<const f32x4*>(vp), x1 = *reinterpret_cast<const f32x4*>(vp + 4);
-#pragma unroll
-          for (int j = 0; j < 4; ++j) {
-            v8[j] += x0[j];
-            v8[4 + j] += x1[j];
-          }
-        }
-      }
-      vec out;
-#pragma unroll
-      for (int j = 0; j < 8; ++j) {
-        elem hi, lo;
-        L::split(v8[j] * sc, &hi, &lo);
-        out[j] = lo_half ? lo : hi;
-      }
-      vb[mt][nt] = out;
-    }
-  }
-
-  // ---- A operand rows: B[rho, :] for this lane's 8 ranks of every rank tile
-  const uint16_t* bp[NT][8];
+  // page rows of B for this lane's 8 ranks of every rank tile
+  const uint16_t* rowp[NT][8];
 #pragma unroll
   for (int nt = 0; nt < NT; ++nt)
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
       const int rho = 16 * nt + 8 * kq + j;
       const int i = pr.b_row_base[ad] + (rho < r ? rho : 0);
-      bp[nt][j] = pool + (int64_t)a.tables[pr.b_tab_off[ad] + i / rpb] * a.block_elems + (int64_t)(i % rpb) * pr.d_out;
+      rowp[nt][j] = pool + (int64_t)a.tables[pr.b_tab_off[ad] + i / rpb] * a.block_elems + (int64_t)(i % rpb) * pr.d_out;
     }
 
-  const int m = lane & 15;
-  for (int o0 = col_begin; o0 < col_end; o0 += 32) {
-    // column of A-operand row m in column tile tau: o0 + 8*(m/4) + 4*tau + m%4
-    f32x4 acc[MT][2];
+  // the slab's columns in pieces of 32*CH, so that the resident fragments stay at 64 registers
+  for (int col_begin = slab_begin; col_begin < slab_begin + c.cols_per_slab && col_begin < pr.d_out;
+       col_begin += 32 * CH) {
+    // ---- A operand: B[rho, col]; column of A-operand row m in column tile tau of a chunk: 8*(m/4) + 4*tau + m%4
+    vec bf[CH][2][NT];
 #pragma unroll
-    for (int mt = 0; mt < MT; ++mt) acc[mt][0] = acc[mt][1] = f32x4{0.f, 0.f, 0.f, 0.f};
+    for (int nt = 0; nt < NT; ++nt)
 #pragma unroll
-    for (int nt = 0; nt < NT; ++nt) {
-      if (16 * nt < r) {
+      for (int ch = 0; ch < CH; ++ch)
 #pragma unroll
         for (int tau = 0; tau < 2; ++tau) {
-          const int col = o0 + 8 * (m >> 2) + 4 * tau + (m & 3);
+          const int col = col_begin + 32 * ch + 8 * (m >> 2) + 4 * tau + (m & 3);
+          const int colc = col < pr.d_out ? col : pr.d_out - 1;
           uint16_t g8[8];
+          // unconditional loads (padding ranks point at a real row), zeroed afterwards: no
+          // divergent branch around each 2-byte gather
 #pragma unroll
-          for (int j = 0; j < 8; ++j) g8[j] = (16 * nt + 8 * kq + j < r) ? bp[nt][j][col] : (uint16_t)0;
-          vec af;
-          __builtin_memcpy(&af, g8, 16);
+          for (int j = 0; j < 8; ++j) g8[j] = rowp[nt][j][colc];
 #pragma unroll
-          for (int mt = 0; mt < MT; ++mt) acc[mt][tau] = L::mfma(af, vb[mt][nt], acc[mt][tau]);
+          for (int j = 0; j < 8; ++j)
+            if (!(16 * nt + 8 * kq + j < r && col < pr.d_out)) g8[j] = 0;
+          __builtin_memcpy(&bf[ch][tau][nt], g8, 16);
         }
+
+    for (int pos_t = pos0; pos_t < pos_stop; pos_t += 16) {
+      const int pos = pos_t + n;
+      const bool tvalid = pos < pos_stop;
+      const int tok = a.perm[tvalid ? pos : pos_stop - 1];
+      uint16_t* yrow = reinterpret_cast<uint16_t*>(pr.y) + (int64_t)tok * pr.ld_y + col_begin + 8 * kg;
+      // the y pieces are requested first so that their latency overlaps the preparation of v
+      u32x4 yraw[CH];
+#pragma unroll
+      for (int ch = 0; ch < CH; ++ch)
+        if (col_begin + 32 * ch < pr.d_out) yraw[ch] = *reinterpret_cast<const u32x4*>(yrow + 32 * ch);
+      // ---- B operand: this token's scaled v, high part in k-slots 0..15, remainder in 16..31
+      vec vb[NT];
+#pragma unroll
+      for (int nt = 0; nt < NT; ++nt) {
+        float v8[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) v8[j] = 0.f;
+        if (16 * nt < r) {
+          for (int ks = 0; ks < c.k_splits; ++ks) {
+            const float* vp =
+                a.v + (((int64_t)ks * c.v_rows + vrow0 + (pos - pos0)) * a.n_proj + p) * RP + 16 * nt + 8 * kq;
+            const f32x4 x0 = *reinterpret_cast<const f32x4*>(vp), x1 = *reinterpret_cast<const f32x4*>(vp + 4);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+              v8[j] += x0[j];
+              v8[4 + j] += x1[j];
+            }
+          }
+        }
+        vec out;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+          elem hi, lo;
+          L::split(v8[j] * sc, &hi, &lo);
+          out[j] = lo_half ? lo : hi;
+        }
+        vb[nt] = out;
       }
-    }
 #pragma unroll
-    for (int mt = 0; mt < MT; ++mt) {
-      if (tvalid[mt]) {
-        uint16_t ys[8];
-        u32x4 raw = *reinterpret_cast<const u32x4*>(yrow[mt] + o0);
-        __builtin_memcpy(ys, &raw, 16);
+      for (int ch = 0; ch < CH; ++ch) {
+        if (col_begin + 32 * ch < pr.d_out) {
+          f32x4 acc0 = {0.f, 0.f, 0.f, 0.f}, acc1 = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-        for (int tau = 0; tau < 2; ++tau)
+          for (int nt = 0; nt < NT; ++nt) {
+            if (16 * nt < r) {
+              acc0 = L::mfma(bf[ch][0][nt], vb[nt], acc0);
+              acc1 = L::mfma(bf[ch][1][nt], vb[nt], acc1);
+            }
+          }
+          if (tvalid) {
+            uint16_t ys[8];
+            __builtin_memcpy(ys, &yraw[ch], 16);
 #pragma unroll
-          for (int i = 0; i < 4; ++i) ys[4 * tau + i] = S::from_float(S::to_float(ys[4 * tau + i]) + acc[mt][tau][i]);
-        __builtin_memcpy(&raw, ys, 16);
-        *reinterpret_cast<u32x4*>(yrow[mt] + o0) = raw;
+            for (int i = 0; i < 4; ++i) {
+              ys[i] = S::from_float(S::to_float(ys[i]) + acc0[i]);
+              ys[4 + i] = S::from_float(S::to_float(ys[4 + i]) + acc1[i]);
+            }
+            u32x4 raw;
+            __builtin_memcpy(&raw, ys, 16);
+            *reinterpret_cast<u32x4*>(yrow + 32 * ch) = raw;
+          }
+        }
       }
     }
   }
@@ -295,8 +316,8 @@ flp_status launch_pair(const FlpLoraArgs& a, const FlpLoraMfma& c, hipStream_t s
   int max_dout = 0;
   for (int p = 0; p < a.n_proj; ++p) max_dout = a.proj[p].d_out > max_dout ? a.proj[p].d_out : max_dout;
   const unsigned slabs = (unsigned)((max_dout + c.cols_per_slab - 1) / c.cols_per_slab);
-  hipLaunchKernelGGL((lora_expand_mfma_kernel<L, MT, NT>), dim3(c.tiles_bound, slabs, a.n_proj), dim3(64), 0, stream,
-                     a, c);
+  hipLaunchKernelGGL((lora_expand_mfma_kernel<L, NT>), dim3(c.groups_bound, slabs, a.n_proj), dim3(64), 0, stream, a,
+                     c);
   FLP_TRY_HIP(hipGetLastError());
   return FLP_OK;
 }

@@ -125,3 +125,53 @@ class GpuStep:
                                          v_new=self.acts["v_new"] if append else None)
         self.torch.cuda.synchronize()
         return to_np(out, self.sd)
+
+
+# ------------------------------------------------------------------ large pools: sparse images
+def compact_step(step):
+    """Pool image that holds only the step's touched blocks, with the tables renumbered to
+    match (block id -> row of `step.content`).  Lets the oracle follow a step whose pool is
+    too large to mirror on the host; relabelling blocks changes no result."""
+    n = int(step.content_ids.max()) + 1 if len(step.content_ids) else 0
+    remap = np.full(n, -1, dtype=np.int64)
+    remap[step.content_ids] = np.arange(len(step.content_ids))
+    kv = np.where(step.kv_tables >= 0, remap[np.maximum(step.kv_tables, 0)], -1).astype(np.int32)
+    lt = remap[step.lora_tables].astype(np.int32)
+    return step.content.copy(), kv, lt
+
+
+class SparseGpuPool:
+    """Tiers of the full size on the GPU machine (device tier left uninitialised except for the
+    step's blocks), for pools far larger than host memory."""
+
+    def __init__(self, step, n_dev_blocks=None, n_host_blocks=None):
+        import torch
+        from paper_2505_03756_amd import flpool
+        cfg = step.cfg
+        self.cfg, self.sd = cfg, wl.storage_dtype(cfg.dtype)
+        nd = cfg.n_dev_blocks if n_dev_blocks is None else n_dev_blocks
+        nh = cfg.n_host_blocks if n_host_blocks is None else n_host_blocks
+        tdt = torch.float32 if cfg.dtype == "f32" else torch.int16
+        self.dev = torch.empty((nd, cfg.block_elems), dtype=tdt, device="cuda")
+        self.host = torch.zeros((nh, cfg.block_elems), dtype=tdt).pin_memory()
+        self.pool = flpool.Pool(cfg.dtype, cfg.n_kv_heads, cfg.head_dim, nd, nh, block_tokens=cfg.block_tokens,
+                                dev=self.dev, host=self.host)
+        swapped = np.isin(step.content_ids, step.swap_in_dev)
+        keep = np.flatnonzero(~swapped)
+        for lo in range(0, len(keep), 1024):
+            sel = keep[lo:lo + 1024]
+            self.dev[torch.from_numpy(step.content_ids[sel].astype(np.int64)).cuda()] = to_dev(step.content[sel])
+        row_of = {int(b): r for r, b in enumerate(step.content_ids)}
+        host_np = self.host.numpy()
+        for h, d in zip(step.swap_in_host, step.swap_in_dev):
+            host_np[h] = step.content[row_of[int(d)]].view(host_np.dtype)
+        if len(step.swap_in_dev):       # the device copies of swapped blocks start as poison
+            idx = torch.from_numpy(step.swap_in_dev.astype(np.int64)).cuda()
+            self.dev[idx] = int(np.array(poison_value(cfg.dtype)).astype(np.int64)) if cfg.dtype != "f32" else float("nan")
+
+    def rows(self, ids):
+        """Device blocks `ids` as a storage array."""
+        import torch
+        torch.cuda.synchronize()
+        out = self.dev[torch.from_numpy(np.asarray(ids).astype(np.int64)).cuda()]
+        return to_np(out, self.sd)

@@ -127,10 +127,15 @@ LORA_CASES = {
     "f16_long_segments": lambda: small_cfg("f16", hidden=1024, n_q_heads=8, n_kv_heads=8, n_seqs=24,
                                            prefix_range=(0, 0), new_range=(40, 180), n_adapters=12, ranks=(16,),
                                            adapter_dist="zipf", n_dev_blocks=600, swap_in_frac=0.0, seed=82),
-    # ranks 8..64 mixed -> four rank tiles with partially filled ones; many short segments
+    # ranks 8..64 mixed -> four rank tiles with partially filled ones; many short segments, 16-token tiles
     "bf16_mixed_rank": lambda: small_cfg("bf16", hidden=1024, n_q_heads=8, n_kv_heads=8, n_seqs=200,
-                                         prefix_range=(0, 0), new_range=(1, 1), decode_frac=1.0, n_adapters=60,
+                                         prefix_range=(0, 0), new_range=(2, 11), n_adapters=60,
                                          ranks=(8, 16, 32, 64), n_dev_blocks=2500, swap_in_frac=0.0, seed=83),
+    # the same shapes as a small decode batch (per-token kernels)
+    "bf16_mixed_rank_decode": lambda: small_cfg("bf16", hidden=1024, n_q_heads=8, n_kv_heads=8, n_seqs=200,
+                                                prefix_range=(0, 0), new_range=(1, 1), decode_frac=1.0,
+                                                n_adapters=60, ranks=(8, 16, 32, 64), n_dev_blocks=2500,
+                                                swap_in_frac=0.0, seed=83),
     # rank 64 with 32-token tiles and a k/v width different from q/o (grouped-query shapes)
     "f16_rank64_gqa": lambda: small_cfg("f16", hidden=1024, n_q_heads=8, n_kv_heads=2, n_seqs=30,
                                         prefix_range=(0, 0), new_range=(30, 120), n_adapters=5, ranks=(64,),
