@@ -5,7 +5,7 @@
 // table), organised as a tiled online-softmax so that K and V are read once per tile of
 // query rows instead of once per row.
 //
-// One workgroup (4 waves) owns up to 4*32*NRT query rows of one (sequence, kv head); row r
+// One workgroup (8 waves, one per CU) owns up to 8*32*NRT query rows of one (sequence, kv head); row r
 // is (new token r / G, query head g*G + r % G), so the G query heads that share a kv head
 // sit in the same tile and K/V are read once for all of them.  It walks the context in
 // tiles of 64 positions (4 pool blocks), staged through LDS and double-buffered.
@@ -19,6 +19,8 @@
 // keys are fed to the first product is permuted (bits 2 and 3 of the key index swapped)
 // so that the 8 keys a lane ends up holding are consecutive positions.
 #include <hip/hip_runtime.h>
+
+#include <type_traits>
 
 #include "flp_internal.h"
 #include "flp_types.h"
@@ -73,7 +75,7 @@ __device__ __forceinline__ V as_vec(u32x4 r) {
 __device__ __forceinline__ int key_of_row(int m) { return (m & 0x13) | ((m & 4) << 1) | ((m & 8) >> 1); }
 
 template <typename M, int NRT>
-__global__ __launch_bounds__(256, 2) void attn_mfma_kernel(FlpAttnArgs a, const FlpMfmaItem* __restrict__ items) {
+__global__ __launch_bounds__(512, 2) void attn_mfma_kernel(FlpAttnArgs a, const FlpMfmaItem* __restrict__ items) {
   typedef typename M::vec vec;
   __shared__ __attribute__((aligned(16))) uint8_t smem[2 * kTileBytes];
 
@@ -130,32 +132,39 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(FlpAttnArgs a, const 
       for (int i = 0; i < 16; ++i) O[nt][dt][i] = 0.f;
   }
 
-  // ---- tile staging: thread -> one K chunk and one V chunk per pool block of the tile
-  const int kkey = tid >> 4, kchunk = tid & 15;      // K: key inside the block, 16-byte chunk of its row
-  const int vd = tid >> 1, vhalf = tid & 1;          // V: channel, which 8 of the 16 slots
+  // ---- tile staging: the tile's 4 pool blocks are split over the two halves of the workgroup;
+  //      a thread moves one K chunk and one V chunk (16 bytes each) of each of its 2 blocks
+  const int sthalf = tid >> 8, st8 = tid & 255;
+  const int kkey = st8 >> 4, kchunk = st8 & 15;      // K: key inside the block, 16-byte chunk of its row
+  const int vd = st8 >> 1, vhalf = st8 & 1;          // V: channel, which 8 of the 16 slots
   const int kswz = ((kkey & 4) << 1) | ((kkey & 8) >> 1) | (kkey & 3);   // = row of the A operand & 15
   const int k_lds = kkey * 256 + ((kchunk ^ kswz) << 4);
   const int v_lds = kKBytes + ((2 * vd + (vhalf ^ ((vd >> 2) & 1) ^ ((vd >> 3) & 1))) << 4);
-  u32x4 kreg[4], vreg[4];
+  // two register sets: while tile kt is being multiplied, tile kt+1 waits in registers for its
+  // LDS buffer and tile kt+2 is in flight from HBM/L2 (one tile of compute is shorter than the
+  // memory latency, so a single tile of look-ahead leaves the loop latency-bound)
+  u32x4 kreg[2][2], vreg[2][2];
 
-  auto load_tile = [&](int kt) {
+  auto load_tile = [&](int kt, int set) {
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
+    for (int uu = 0; uu < 2; ++uu) {
+      const int u = 2 * sthalf + uu;
       int bi = 4 * kt + u;
       bi = bi < nblk_valid ? bi : nblk_valid - 1;
       const uint16_t* base = pool + (int64_t)table[bi] * a.block_elems;
-      kreg[u] = *reinterpret_cast<const u32x4*>(base + ((int64_t)g * BT + kkey) * D + 8 * kchunk);
-      vreg[u] = *reinterpret_cast<const u32x4*>(base + v_region + 8 * tid);
+      kreg[set][uu] = *reinterpret_cast<const u32x4*>(base + ((int64_t)g * BT + kkey) * D + 8 * kchunk);
+      vreg[set][uu] = *reinterpret_cast<const u32x4*>(base + v_region + 8 * st8);
     }
   };
-  auto store_tile = [&](int kt, uint8_t* buf) {
+  auto store_tile = [&](int kt, uint8_t* buf, int set) {
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
-      *reinterpret_cast<u32x4*>(buf + u * 4096 + k_lds) = kreg[u];
+    for (int uu = 0; uu < 2; ++uu) {
+      const int u = 2 * sthalf + uu;
+      *reinterpret_cast<u32x4*>(buf + u * 4096 + k_lds) = kreg[set][uu];
       // slots at or past the sequence's length hold arbitrary bits: zero them so that a
       // zero weight times such a value cannot turn into NaN
       const int pos0 = BN * kt + BT * u + 8 * vhalf;
-      u32x4 v = vreg[u];
+      u32x4 v = vreg[set][uu];
       if (pos0 + 8 > L) {
         uint16_t e[8];
         __builtin_memcpy(e, &v, 16);
@@ -168,17 +177,19 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(FlpAttnArgs a, const 
     }
   };
 
-  load_tile(0);
-  store_tile(0, smem);
+  load_tile(0, 0);
+  store_tile(0, smem, 0);
+  if (n_tiles > 1) load_tile(1, 1);
   __syncthreads();
 
   const int krow = key_of_row(lr);                    // this lane's key inside a 32-key sub-tile
   const int a_swz = lr & 15;
 
-  for (int kt = 0; kt < n_tiles; ++kt) {
+  // one tile step; J (compile-time) is the register set that held tile kt
+  auto tile_step = [&](auto J, const int kt) {
+    constexpr int j = decltype(J)::value;
     uint8_t* buf = smem + (kt & 1) * kTileBytes;
-    const bool more = kt + 1 < n_tiles;
-    if (more) load_tile(kt + 1);
+    if (kt + 2 < n_tiles) load_tile(kt + 2, j);        // set j held tile kt, already in LDS
 
     if (wave_active && BN * kt <= wave_max_pos) {
       // ---- S^T = K Q^T for the tile's two 32-key sub-tiles
@@ -284,8 +295,12 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(FlpAttnArgs a, const 
       }
     }
 
-    if (more) store_tile(kt + 1, smem + ((kt + 1) & 1) * kTileBytes);
+    if (kt + 1 < n_tiles) store_tile(kt + 1, smem + ((kt + 1) & 1) * kTileBytes, (j + 1) % 2);
     __syncthreads();
+  };
+  for (int kt0 = 0; kt0 < n_tiles; kt0 += 2) {
+    tile_step(std::integral_constant<int, 0>{}, kt0);
+    if (kt0 + 1 < n_tiles) tile_step(std::integral_constant<int, 1>{}, kt0 + 1);
   }
 
   // ---- normalise and store: lane (row, half) holds channels 32dt + 8q + 4hf + (0..3)
@@ -318,9 +333,9 @@ flp_status flp_launch_attn_mfma(int dtype, const FlpAttnArgs& a, const FlpMfmaIt
                                 hipStream_t stream) {
   if (n_items <= 0) return FLP_OK;
   if (dtype == FLP_F16)
-    hipLaunchKernelGGL((attn_mfma_kernel<MF16, 1>), dim3(n_items), dim3(256), 0, stream, a, items_dev);
+    hipLaunchKernelGGL((attn_mfma_kernel<MF16, 1>), dim3(n_items), dim3(512), 0, stream, a, items_dev);
   else if (dtype == FLP_BF16)
-    hipLaunchKernelGGL((attn_mfma_kernel<MBF16, 1>), dim3(n_items), dim3(256), 0, stream, a, items_dev);
+    hipLaunchKernelGGL((attn_mfma_kernel<MBF16, 1>), dim3(n_items), dim3(512), 0, stream, a, items_dev);
   else {
     flp_set_error("attention (matrix-core path): dtype %d not supported", dtype);
     return FLP_ENOTSUP;

@@ -151,7 +151,7 @@ extern "C" flp_status flp_paged_prefix_attention(flp_pool* p, const flp_attn_bat
 
   // Two kinds of work.  Sequences with at least 8 query rows per kv head (prefill, or decode
   // under grouped-query attention) on a 16-bit pool with head_dim 128 go to the matrix-core
-  // kernel in tiles of 128 rows; everything else (fp32, head_dim 64, single-row decode) goes to
+  // kernel in tiles of 256 rows; everything else (fp32, head_dim 64, single-row decode) goes to
   // the row-streaming kernel in runs of up to 4 tokens.  Both lists are ordered heaviest first.
   const bool mfma_ok = p->cfg.dtype != FLP_F32 && p->cfg.head_dim == 128;
   const int G = b->n_q_heads / p->cfg.n_kv_heads;

@@ -114,7 +114,7 @@ flp_status flp_launch_attn_rows(int dtype, int head_dim, const FlpAttnArgs& a, c
 
 flp_status flp_launch_attn_mfma(int dtype, const FlpAttnArgs& a, const FlpMfmaItem* items_dev, int32_t n_items,
                                 hipStream_t stream);
-constexpr int kMfmaRowsPerItem = 128;
+constexpr int kMfmaRowsPerItem = 256;
 
 struct FlpLoraArgs {
   const uint8_t* pool;
