@@ -27,6 +27,11 @@ sys.path.insert(0, ROOT)
 sys.path.insert(0, os.path.join(ROOT, "tests"))
 
 HBM_PEAK_GBS = 8000.0        # MI355X HBM3E, published
+# HBM bytes per launch of the dominant kernel, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this
+# file (profiles/attn_mfma_7b_prefill_pmc.md), scaled by what the same counters read for a plain
+# device-to-device copy of 1 GiB (FETCH_SIZE reads half the bytes, WRITE_SIZE all of them).  Only
+# valid for the default workload and seed; null otherwise.
+MEASURED_TRAFFIC = {("7b_prefill", 20250504): 1.603e9, ("7b_decode", 20250505): None}
 MFMA_PEAK_TFLOPS = 2500.0    # dense fp16 / bf16 MFMA, published
 PCIE_PEAK_GBS = 64.0         # PCIe Gen5 x16, one direction
 
@@ -83,7 +88,7 @@ def main():
         gp.pool.free(rng.permutation(ids), tier)
 
     # ---- two batches with disjoint blocks (ids handed out by the library's allocator)
-    n_sets = 2
+    n_sets = 2 if cfg.swap_in_frac > 0 or cfg.swap_out_frac > 0 else 1     # nothing to overlap without swaps
     sets = []
     host_np = gp.host.numpy()
     for i in range(n_sets):
@@ -245,13 +250,18 @@ def main():
     a = kernels["attention"]
     t_hbm = a["bytes"] / (HBM_PEAK_GBS * 1e9)
     t_mfma = a["flops"] / (MFMA_PEAK_TFLOPS * 1e12)
+    traffic = MEASURED_TRAFFIC.get((cfg.name, seed))
+    kname = "attn_mfma_kernel" if (cfg.dtype != "f32" and cfg.head_dim == 128 and
+                                   int(N.max()) * (n_h // n_kv) >= 8) else "attn_rows_kernel"
     if cfg.dtype != "f32" and t_mfma > t_hbm:
         roof = {"bound": "mfma", "achieved": a["TFLOPps"], "peak": MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
-                "frac": round(a["TFLOPps"] / MFMA_PEAK_TFLOPS, 4), "traffic": None, "kernel": "attn_mfma_kernel",
+                "frac": round(a["TFLOPps"] / MFMA_PEAK_TFLOPS, 4), "traffic": traffic, "kernel": kname,
                 "hbm_frac_of_same_launch": a["frac_of_peak"]}
     else:
         roof = {"bound": "hbm", "achieved": a["GBps"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "frac": round(a["GBps"] / HBM_PEAK_GBS, 4), "traffic": None, "kernel": "attention"}
+                "frac": round(a["GBps"] / HBM_PEAK_GBS, 4), "traffic": traffic, "kernel": kname,
+                "algorithmic_bytes": a["bytes"], "mfma_TFLOPps_of_same_launch": a["TFLOPps"],
+                "mfma_frac_of_same_launch": round(a["TFLOPps"] / MFMA_PEAK_TFLOPS, 4)}
 
     compute_ms = sum(v for k, v in stage_ms.items() if k != "swap")
     out = {
@@ -272,7 +282,8 @@ def main():
                    "ranks": sorted(set(int(r) for r in step.rank[active])),
                    "swap_in_blocks": [int(len(r.step.swap_in_dev)) for r in runners], "block_bytes": cfg.block_bytes,
                    "base_gemm": "excluded (y arrives holding x.W)",
-                   "swap": "own stream, overlapped with the previous batch's compute (two alternating batches)"},
+                   "swap": ("own stream, overlapped with the previous batch's compute (two alternating batches)"
+                            if n_sets == 2 else "none in this workload")},
         "roofline": roof,
         "kernels": kernels,
         "serialised": {"ms_per_step": round(serial_ms, 4), "tokens_per_s": round(T / (serial_ms * 1e-3), 1),

@@ -225,8 +225,11 @@ def make_step(cfg: LayerConfig, seed: Optional[int] = None,
     be = cfg.block_elems
     bt = cfg.block_tokens
 
+    # (the id permutations are always drawn, so that a step has the same lengths and adapters
+    # whoever hands out the block ids)
+    perm_d = rng.permutation(cfg.n_dev_blocks).astype(np.int32)
+    perm_h = rng.permutation(cfg.n_host_blocks).astype(np.int32)
     if alloc_dev is None:
-        perm_d = rng.permutation(cfg.n_dev_blocks).astype(np.int32)
         cur_d = [0]
 
         def alloc_dev(n):
@@ -236,7 +239,6 @@ def make_step(cfg: LayerConfig, seed: Optional[int] = None,
             cur_d[0] += n
             return out
     if alloc_host is None:
-        perm_h = rng.permutation(cfg.n_host_blocks).astype(np.int32)
         cur_h = [0]
 
         def alloc_host(n):
