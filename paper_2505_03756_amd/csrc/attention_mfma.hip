@@ -134,7 +134,8 @@ __global__ __launch_bounds__(512, 2) void attn_mfma_kernel(FlpAttnArgs a, const 
 
   // ---- tile staging: the tile's 4 pool blocks are split over the two halves of the workgroup;
   //      a thread moves one K chunk and one V chunk (16 bytes each) of each of its 2 blocks
-  const int sthalf = tid >> 8, st8 = tid & 255;
+  const int sthalf = __builtin_amdgcn_readfirstlane(tid >> 8);   // wave-uniform: table lookups stay scalar
+  const int st8 = tid & 255;
   const int kkey = st8 >> 4, kchunk = st8 & 15;      // K: key inside the block, 16-byte chunk of its row
   const int vd = st8 >> 1, vhalf = st8 & 1;          // V: channel, which 8 of the 16 slots
   const int kswz = ((kkey & 4) << 1) | ((kkey & 8) >> 1) | (kkey & 3);   // = row of the A operand & 15
@@ -144,16 +145,27 @@ __global__ __launch_bounds__(512, 2) void attn_mfma_kernel(FlpAttnArgs a, const 
   // LDS buffer and tile kt+2 is in flight from HBM/L2 (one tile of compute is shorter than the
   // memory latency, so a single tile of look-ahead leaves the loop latency-bound)
   u32x4 kreg[2][2], vreg[2][2];
+  const uint32_t k_goff = (uint32_t)(kkey * D + 8 * kchunk), v_goff = (uint32_t)(8 * st8);   // per-lane element offsets
 
-  auto load_tile = [&](int kt, int set) {
+  // the block ids of a tile are read from the table one step before the loads that need them:
+  // a table lookup at the top of every step would put a dependent memory latency in front of
+  // the step's compute
+  int32_t ids_next[2];
+  auto fetch_ids = [&](int kt) {
 #pragma unroll
     for (int uu = 0; uu < 2; ++uu) {
-      const int u = 2 * sthalf + uu;
-      int bi = 4 * kt + u;
+      int bi = 4 * kt + 2 * sthalf + uu;
       bi = bi < nblk_valid ? bi : nblk_valid - 1;
-      const uint16_t* base = pool + (int64_t)table[bi] * a.block_elems;
-      kreg[set][uu] = *reinterpret_cast<const u32x4*>(base + ((int64_t)g * BT + kkey) * D + 8 * kchunk);
-      vreg[set][uu] = *reinterpret_cast<const u32x4*>(base + v_region + 8 * st8);
+      ids_next[uu] = table[bi];
+    }
+  };
+  auto load_tile = [&](int set) {                      // loads the tile whose ids are in ids_next
+#pragma unroll
+    for (int uu = 0; uu < 2; ++uu) {
+      const uint16_t* kbase = pool + (int64_t)ids_next[uu] * a.block_elems + (int64_t)g * BT * D;   // uniform
+      const uint16_t* vbase = pool + (int64_t)ids_next[uu] * a.block_elems + v_region;               // uniform
+      kreg[set][uu] = *reinterpret_cast<const u32x4*>(kbase + k_goff);
+      vreg[set][uu] = *reinterpret_cast<const u32x4*>(vbase + v_goff);
     }
   };
   auto store_tile = [&](int kt, uint8_t* buf, int set) {
@@ -177,9 +189,12 @@ __global__ __launch_bounds__(512, 2) void attn_mfma_kernel(FlpAttnArgs a, const 
     }
   };
 
-  load_tile(0, 0);
+  fetch_ids(0);
+  load_tile(0);
+  fetch_ids(1);                                        // (clamped to the last valid block when there is no tile 1)
   store_tile(0, smem, 0);
-  if (n_tiles > 1) load_tile(1, 1);
+  if (n_tiles > 1) load_tile(1);
+  fetch_ids(2);
   __syncthreads();
 
   const int krow = key_of_row(lr);                    // this lane's key inside a 32-key sub-tile
@@ -189,7 +204,8 @@ __global__ __launch_bounds__(512, 2) void attn_mfma_kernel(FlpAttnArgs a, const 
   auto tile_step = [&](auto J, const int kt) {
     constexpr int j = decltype(J)::value;
     uint8_t* buf = smem + (kt & 1) * kTileBytes;
-    if (kt + 2 < n_tiles) load_tile(kt + 2, j);        // set j held tile kt, already in LDS
+    if (kt + 2 < n_tiles) load_tile(j);                // tile kt+2 into set j (it held tile kt, already in LDS)
+    fetch_ids(kt + 3);
 
     if (wave_active && BN * kt <= wave_max_pos) {
       // ---- S^T = K Q^T for the tile's two 32-key sub-tiles
