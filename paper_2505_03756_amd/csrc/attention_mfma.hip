@@ -78,6 +78,7 @@ template <typename M, int NRT>
 __global__ __launch_bounds__(512, 2) void attn_mfma_kernel(FlpAttnArgs a, const FlpMfmaItem* __restrict__ items) {
   typedef typename M::vec vec;
   __shared__ __attribute__((aligned(16))) uint8_t smem[2 * kTileBytes];
+  __shared__ int32_t tab_lds[kMfmaMaxBlocks];          // this sequence's block table
 
   const FlpMfmaItem it = items[blockIdx.x];
   if (it.n_rows <= 0) return;
@@ -147,16 +148,17 @@ __global__ __launch_bounds__(512, 2) void attn_mfma_kernel(FlpAttnArgs a, const 
   u32x4 kreg[2][2], vreg[2][2];
   const uint32_t k_goff = (uint32_t)(kkey * D + 8 * kchunk), v_goff = (uint32_t)(8 * st8);   // per-lane element offsets
 
-  // the block ids of a tile are read from the table one step before the loads that need them:
-  // a table lookup at the top of every step would put a dependent memory latency in front of
-  // the step's compute
+  // The sequence's block table is copied into LDS once; the per-tile lookups then cost an LDS
+  // read instead of a scalar load from memory (whose latency every later LDS wait would inherit,
+  // because scalar loads and LDS reads share one completion counter).
+  for (int i = tid; i < nblk_valid; i += 512) tab_lds[i] = table[i];
   int32_t ids_next[2];
   auto fetch_ids = [&](int kt) {
 #pragma unroll
     for (int uu = 0; uu < 2; ++uu) {
       int bi = 4 * kt + 2 * sthalf + uu;
       bi = bi < nblk_valid ? bi : nblk_valid - 1;
-      ids_next[uu] = table[bi];
+      ids_next[uu] = __builtin_amdgcn_readfirstlane(tab_lds[bi]);
     }
   };
   auto load_tile = [&](int set) {                      // loads the tile whose ids are in ids_next
@@ -189,6 +191,7 @@ __global__ __launch_bounds__(512, 2) void attn_mfma_kernel(FlpAttnArgs a, const 
     }
   };
 
+  __syncthreads();
   fetch_ids(0);
   load_tile(0);
   fetch_ids(1);                                        // (clamped to the last valid block when there is no tile 1)

@@ -175,7 +175,8 @@ extern "C" flp_status flp_paged_prefix_attention(flp_pool* p, const flp_attn_bat
   for (int32_t i : seq_order) {
     const int32_t n = b->cu_new[i + 1] - b->cu_new[i];
     if (n <= 0) continue;
-    if (mfma_ok && (int64_t)G * n >= 8) {
+    const int64_t blocks_i = ((int64_t)b->prefix_len[i] + n + p->cfg.block_tokens - 1) / p->cfg.block_tokens;
+    if (mfma_ok && (int64_t)G * n >= 8 && blocks_i <= kMfmaMaxBlocks) {
       const int32_t R = G * n;
       for (int g = 0; g < n_kv; ++g) {
         for (int32_t r0 = 0; r0 < R; r0 += kMfmaRowsPerItem)

@@ -115,6 +115,7 @@ flp_status flp_launch_attn_rows(int dtype, int head_dim, const FlpAttnArgs& a, c
 flp_status flp_launch_attn_mfma(int dtype, const FlpAttnArgs& a, const FlpMfmaItem* items_dev, int32_t n_items,
                                 hipStream_t stream);
 constexpr int kMfmaRowsPerItem = 256;
+constexpr int kMfmaMaxBlocks = 4096;       // longest context of the matrix-core kernel: 65536 positions
 
 struct FlpLoraArgs {
   const uint8_t* pool;
