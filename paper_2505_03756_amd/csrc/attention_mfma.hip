@@ -75,7 +75,7 @@ __device__ __forceinline__ V as_vec(u32x4 r) {
 __device__ __forceinline__ int key_of_row(int m) { return (m & 0x13) | ((m & 4) << 1) | ((m & 8) >> 1); }
 
 template <typename M, int NRT>
-__global__ __launch_bounds__(512, 2) void attn_mfma_kernel(FlpAttnArgs a, const FlpMfmaItem* __restrict__ items) {
+__global__ __launch_bounds__(NRT == 1 ? 512 : 256, NRT == 1 ? 2 : 1) void attn_mfma_kernel(FlpAttnArgs a, const FlpMfmaItem* __restrict__ items) {
   typedef typename M::vec vec;
   __shared__ __attribute__((aligned(16))) uint8_t smem[2 * kTileBytes];
   __shared__ int32_t tab_lds[kMfmaMaxBlocks];          // this sequence's block table
@@ -135,6 +135,8 @@ __global__ __launch_bounds__(512, 2) void attn_mfma_kernel(FlpAttnArgs a, const 
 
   // ---- tile staging: the tile's 4 pool blocks are split over the two halves of the workgroup;
   //      a thread moves one K chunk and one V chunk (16 bytes each) of each of its 2 blocks
+  constexpr int NTHR = NRT == 1 ? 512 : 256;          // 8 waves x 32 rows or 4 waves x 64 rows
+  constexpr int BPT = 1024 / NTHR;                    // pool blocks of a tile staged per thread
   const int sthalf = __builtin_amdgcn_readfirstlane(tid >> 8);   // wave-uniform: table lookups stay scalar
   const int st8 = tid & 255;
   const int kkey = st8 >> 4, kchunk = st8 & 15;      // K: key inside the block, 16-byte chunk of its row
@@ -145,25 +147,25 @@ __global__ __launch_bounds__(512, 2) void attn_mfma_kernel(FlpAttnArgs a, const 
   // two register sets: while tile kt is being multiplied, tile kt+1 waits in registers for its
   // LDS buffer and tile kt+2 is in flight from HBM/L2 (one tile of compute is shorter than the
   // memory latency, so a single tile of look-ahead leaves the loop latency-bound)
-  u32x4 kreg[2][2], vreg[2][2];
+  u32x4 kreg[2][BPT], vreg[2][BPT];
   const uint32_t k_goff = (uint32_t)(kkey * D + 8 * kchunk), v_goff = (uint32_t)(8 * st8);   // per-lane element offsets
 
   // The sequence's block table is copied into LDS once; the per-tile lookups then cost an LDS
   // read instead of a scalar load from memory (whose latency every later LDS wait would inherit,
   // because scalar loads and LDS reads share one completion counter).
-  for (int i = tid; i < nblk_valid; i += 512) tab_lds[i] = table[i];
-  int32_t ids_next[2];
+  for (int i = tid; i < nblk_valid; i += NTHR) tab_lds[i] = table[i];
+  int32_t ids_next[BPT];
   auto fetch_ids = [&](int kt) {
 #pragma unroll
-    for (int uu = 0; uu < 2; ++uu) {
-      int bi = 4 * kt + 2 * sthalf + uu;
+    for (int uu = 0; uu < BPT; ++uu) {
+      int bi = 4 * kt + BPT * sthalf + uu;
       bi = bi < nblk_valid ? bi : nblk_valid - 1;
       ids_next[uu] = __builtin_amdgcn_readfirstlane(tab_lds[bi]);
     }
   };
   auto load_tile = [&](int set) {                      // loads the tile whose ids are in ids_next
 #pragma unroll
-    for (int uu = 0; uu < 2; ++uu) {
+    for (int uu = 0; uu < BPT; ++uu) {
       const uint16_t* kbase = pool + (int64_t)ids_next[uu] * a.block_elems + (int64_t)g * BT * D;   // uniform
       const uint16_t* vbase = pool + (int64_t)ids_next[uu] * a.block_elems + v_region;               // uniform
       kreg[set][uu] = *reinterpret_cast<const u32x4*>(kbase + k_goff);
@@ -172,8 +174,8 @@ __global__ __launch_bounds__(512, 2) void attn_mfma_kernel(FlpAttnArgs a, const 
   };
   auto store_tile = [&](int kt, uint8_t* buf, int set) {
 #pragma unroll
-    for (int uu = 0; uu < 2; ++uu) {
-      const int u = 2 * sthalf + uu;
+    for (int uu = 0; uu < BPT; ++uu) {
+      const int u = BPT * sthalf + uu;
       *reinterpret_cast<u32x4*>(buf + u * 4096 + k_lds) = kreg[set][uu];
       // slots at or past the sequence's length hold arbitrary bits: zero them so that a
       // zero weight times such a value cannot turn into NaN
