@@ -276,7 +276,7 @@ extern "C" flp_status flp_lora_apply_paged(flp_pool* p, const flp_lora_batch* b,
   hipStream_t stream = (hipStream_t)hip_stream;
   const size_t T = (size_t)b->n_tokens;
 
-  // Matrix-core path for 16-bit pools when every width is a multiple of the 32-wide tiles and
+  // Matrix-core path for 16-bit pools when every width is a multiple of the tile widths (32 in, 64 out) and
   // the batch is large enough for token tiles to fill (prefill); otherwise the vector-ALU
   // kernels: fp32 pools, odd widths, and small decode batches, where a segment is a handful of
   // tokens and the per-token kernels (measured on 256 tokens over 92 adapters: 0.11 ms against
@@ -284,7 +284,7 @@ extern "C" flp_status flp_lora_apply_paged(flp_pool* p, const flp_lora_batch* b,
   bool mfma_ok = p->cfg.dtype != FLP_F32 && b->d_in % 32 == 0 && b->n_tokens >= 1024;
   int max_dout = 0;
   for (int q = 0; q < b->n_proj; ++q) {
-    mfma_ok = mfma_ok && b->proj[q].d_out % 32 == 0;
+    mfma_ok = mfma_ok && b->proj[q].d_out % 64 == 0;
     max_dout = std::max(max_dout, b->proj[q].d_out);
   }
   FlpLoraMfma c{};

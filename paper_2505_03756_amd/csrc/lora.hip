@@ -43,18 +43,26 @@ __global__ __launch_bounds__(1024) void lora_segment_kernel(int32_t T, const int
   // one or two distinct ids per 64 tokens; no atomics, each wave owns its row of counters)
   {
     volatile int32_t* cnt_row = whist + wave * n_ad;
-    for (int t0 = lo; t0 < hi; t0 += 64) {
-      const int t = t0 + lane;
-      const int a = t < hi ? token_adapter[t] : -1;
-      const bool valid = a >= 0 && a < n_ad;
-      uint64_t remaining = __ballot(valid);
-      while (remaining) {
-        const int leader = __ffsll((long long)remaining) - 1;
-        const int v = __shfl(a, leader);
-        const uint64_t same = __ballot(valid && a == v);
-        if (lane == leader) cnt_row[v] = cnt_row[v] + __popcll(same);
-        __builtin_amdgcn_wave_barrier();
-        remaining &= ~same;
+    for (int tb = lo; tb < hi; tb += 64 * 8) {        // 8 loads in flight per lane, then their 8 ballot rounds
+      int a8[8];
+#pragma unroll
+      for (int k = 0; k < 8; ++k) {
+        const int t = tb + 64 * k + lane;
+        a8[k] = t < hi ? token_adapter[t] : -1;
+      }
+#pragma unroll
+      for (int k = 0; k < 8; ++k) {
+        const int a = a8[k];
+        const bool valid = a >= 0 && a < n_ad;
+        uint64_t remaining = __ballot(valid);
+        while (remaining) {
+          const int leader = __ffsll((long long)remaining) - 1;
+          const int v = __shfl(a, leader);
+          const uint64_t same = __ballot(valid && a == v);
+          if (lane == leader) cnt_row[v] = cnt_row[v] + __popcll(same);
+          __builtin_amdgcn_wave_barrier();
+          remaining &= ~same;
+        }
       }
     }
   }
@@ -155,21 +163,30 @@ __global__ __launch_bounds__(1024) void lora_segment_kernel(int32_t T, const int
 
   // placement: each wave walks its range in order, 64 tokens at a time
   volatile int32_t* cur = whist + wave * n_ad;
-  for (int t0 = lo; t0 < hi; t0 += 64) {
-    const int t = t0 + lane;
-    int a = t < hi ? token_adapter[t] : -1;
-    const bool valid = a >= 0 && a < n_ad;
-    uint64_t remaining = __ballot(valid);
-    while (remaining) {
-      const int leader = __ffsll((long long)remaining) - 1;
-      const int v = __shfl(a, leader);
-      const uint64_t same = __ballot(valid && a == v);
-      const int before = cur[v];
-      if (valid && a == v) perm[seg_off[v] + before + __popcll(same & ((1ull << lane) - 1))] = t;
-      __builtin_amdgcn_wave_barrier();
-      if (lane == leader) cur[v] = before + __popcll(same);
-      __builtin_amdgcn_wave_barrier();
-      remaining &= ~same;
+  for (int tb = lo; tb < hi; tb += 64 * 8) {
+    int a8[8];
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+      const int t = tb + 64 * k + lane;
+      a8[k] = t < hi ? token_adapter[t] : -1;
+    }
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+      const int t = tb + 64 * k + lane;
+      const int a = a8[k];
+      const bool valid = a >= 0 && a < n_ad;
+      uint64_t remaining = __ballot(valid);
+      while (remaining) {
+        const int leader = __ffsll((long long)remaining) - 1;
+        const int v = __shfl(a, leader);
+        const uint64_t same = __ballot(valid && a == v);
+        const int before = cur[v];
+        if (valid && a == v) perm[seg_off[v] + before + __popcll(same & ((1ull << lane) - 1))] = t;
+        __builtin_amdgcn_wave_barrier();
+        if (lane == leader) cur[v] = before + __popcll(same);
+        __builtin_amdgcn_wave_barrier();
+        remaining &= ~same;
+      }
     }
   }
 }

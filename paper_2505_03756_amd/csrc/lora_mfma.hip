@@ -177,7 +177,7 @@ __global__ __launch_bounds__(64) void lora_expand_mfma_kernel(FlpLoraArgs a, Flp
   typedef typename L::vec vec;
   typedef typename L::elem elem;
   typedef typename L::S S;
-  constexpr int CH = 8 / NT;                          // 32-column chunks per slab
+  constexpr int CH = 8 / NT;                          // 32-column chunks per resident piece
   const int group = blockIdx.x, slab = blockIdx.y, p = blockIdx.z;
   const int n_seg = *a.n_seg;
   if (group >= a.group_start[n_seg]) return;
@@ -210,18 +210,21 @@ __global__ __launch_bounds__(64) void lora_expand_mfma_kernel(FlpLoraArgs a, Flp
       rowp[nt][j] = pool + (int64_t)a.tables[pr.b_tab_off[ad] + i / rpb] * a.block_elems + (int64_t)(i % rpb) * pr.d_out;
     }
 
-  // the slab's columns in pieces of 32*CH, so that the resident fragments stay at 64 registers
+  // the slab's columns in pieces of 64*C64, so that the resident fragments stay at 64 registers
+  constexpr int C64 = CH / 2;                         // 64-column chunks per piece
   for (int col_begin = slab_begin; col_begin < slab_begin + c.cols_per_slab && col_begin < pr.d_out;
-       col_begin += 32 * CH) {
-    // ---- A operand: B[rho, col]; column of A-operand row m in column tile tau of a chunk: 8*(m/4) + 4*tau + m%4
-    vec bf[CH][2][NT];
+       col_begin += 64 * C64) {
+    // ---- A operand: B[rho, col].  Four column tiles of a 64-column chunk are interleaved: row m of
+    //      tile tau is column 16*(m/4) + 4*tau + m%4, so a lane's 16 results are 16 consecutive columns
+    //      (32 bytes) and the four lanes of a token row cover one full 128-byte line of y.
+    vec bf[C64][4][NT];
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt)
 #pragma unroll
-      for (int ch = 0; ch < CH; ++ch)
+      for (int ch = 0; ch < C64; ++ch)
 #pragma unroll
-        for (int tau = 0; tau < 2; ++tau) {
-          const int col = col_begin + 32 * ch + 8 * (m >> 2) + 4 * tau + (m & 3);
+        for (int tau = 0; tau < 4; ++tau) {
+          const int col = col_begin + 64 * ch + 16 * (m >> 2) + 4 * tau + (m & 3);
           const int colc = col < pr.d_out ? col : pr.d_out - 1;
           uint16_t g8[8];
           // unconditional loads (padding ranks point at a real row), zeroed afterwards: no
@@ -234,16 +237,22 @@ __global__ __launch_bounds__(64) void lora_expand_mfma_kernel(FlpLoraArgs a, Flp
           __builtin_memcpy(&bf[ch][tau][nt], g8, 16);
         }
 
+    int tok = a.perm[pos0 + n < pos_stop ? pos0 + n : pos_stop - 1];
     for (int pos_t = pos0; pos_t < pos_stop; pos_t += 16) {
       const int pos = pos_t + n;
       const bool tvalid = pos < pos_stop;
-      const int tok = a.perm[tvalid ? pos : pos_stop - 1];
-      uint16_t* yrow = reinterpret_cast<uint16_t*>(pr.y) + (int64_t)tok * pr.ld_y + col_begin + 8 * kg;
-      // the y pieces are requested first so that their latency overlaps the preparation of v
-      u32x4 yraw[CH];
+      uint16_t* yrow = reinterpret_cast<uint16_t*>(pr.y) + (int64_t)tok * pr.ld_y + col_begin + 16 * kg;
+      // the y pieces are requested first so that their latency overlaps the preparation of v;
+      // the next sub-tile's token index is fetched now as well
+      u32x4 yraw[C64][2];
 #pragma unroll
-      for (int ch = 0; ch < CH; ++ch)
-        if (col_begin + 32 * ch < pr.d_out) yraw[ch] = *reinterpret_cast<const u32x4*>(yrow + 32 * ch);
+      for (int ch = 0; ch < C64; ++ch)
+        if (col_begin + 64 * ch < pr.d_out) {
+          yraw[ch][0] = *reinterpret_cast<const u32x4*>(yrow + 64 * ch);
+          yraw[ch][1] = *reinterpret_cast<const u32x4*>(yrow + 64 * ch + 8);
+        }
+      const int pos_n = pos + 16;
+      const int tok_next = a.perm[pos_n < pos_stop ? pos_n : pos_stop - 1];
       // ---- B operand: this token's scaled v, high part in k-slots 0..15, remainder in 16..31
       vec vb[NT];
 #pragma unroll
@@ -273,30 +282,33 @@ __global__ __launch_bounds__(64) void lora_expand_mfma_kernel(FlpLoraArgs a, Flp
         vb[nt] = out;
       }
 #pragma unroll
-      for (int ch = 0; ch < CH; ++ch) {
-        if (col_begin + 32 * ch < pr.d_out) {
-          f32x4 acc0 = {0.f, 0.f, 0.f, 0.f}, acc1 = {0.f, 0.f, 0.f, 0.f};
+      for (int ch = 0; ch < C64; ++ch) {
+        if (col_begin + 64 * ch < pr.d_out) {
+          f32x4 acc[4];
+#pragma unroll
+          for (int tau = 0; tau < 4; ++tau) acc[tau] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
           for (int nt = 0; nt < NT; ++nt) {
             if (16 * nt < r) {
-              acc0 = L::mfma(bf[ch][0][nt], vb[nt], acc0);
-              acc1 = L::mfma(bf[ch][1][nt], vb[nt], acc1);
+#pragma unroll
+              for (int tau = 0; tau < 4; ++tau) acc[tau] = L::mfma(bf[ch][tau][nt], vb[nt], acc[tau]);
             }
           }
           if (tvalid) {
-            uint16_t ys[8];
-            __builtin_memcpy(ys, &yraw[ch], 16);
+            uint16_t ys[16];
+            __builtin_memcpy(ys, &yraw[ch][0], 32);
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-              ys[i] = S::from_float(S::to_float(ys[i]) + acc0[i]);
-              ys[4 + i] = S::from_float(S::to_float(ys[4 + i]) + acc1[i]);
-            }
-            u32x4 raw;
-            __builtin_memcpy(&raw, ys, 16);
-            *reinterpret_cast<u32x4*>(yrow + 32 * ch) = raw;
+            for (int tau = 0; tau < 4; ++tau)
+#pragma unroll
+              for (int i = 0; i < 4; ++i) ys[4 * tau + i] = S::from_float(S::to_float(ys[4 * tau + i]) + acc[tau][i]);
+            u32x4 raw[2];
+            __builtin_memcpy(raw, ys, 32);
+            *reinterpret_cast<u32x4*>(yrow + 64 * ch) = raw[0];
+            *reinterpret_cast<u32x4*>(yrow + 64 * ch + 8) = raw[1];
           }
         }
       }
+      tok = tok_next;
     }
   }
 }
