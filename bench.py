@@ -263,6 +263,44 @@ def main():
                 "algorithmic_bytes": a["bytes"], "mfma_TFLOPps_of_same_launch": a["TFLOPps"],
                 "mfma_frac_of_same_launch": round(a["TFLOPps"] / MFMA_PEAK_TFLOPS, 4)}
 
+    # ---- the same LoRA calls with the dense base projection computed by the library (w_base given);
+    #      reported on the side: the base model is not part of the pool's hot path
+    base_info = None
+    if cfg.dtype != "f32":
+        wq = {n: torch.randn(step.proj[n].d_in, step.proj[n].d_out, device="cuda", dtype=torch.float16)
+              .mul_(step.proj[n].d_in ** -0.5).to(torch.float16 if cfg.dtype == "f16" else torch.bfloat16)
+              .view(torch.int16) for n in cfg.projections}
+        g0 = r0.g
+
+        def qkv_b(st):
+            g0.pool.lora_apply_paged(g0.acts["x"], g0.token_adapter, g0.rank, g0.scale, g0.lora_tables,
+                                     [dict(r0.pj(n), w_base=wq[n]) for n in names_qkv], n_tokens=T, d_in=cfg.hidden,
+                                     n_adapters=r0.n_ad, max_rank=r0.max_rank, stream=st)
+
+        def o_b(st):
+            g0.pool.lora_apply_paged(r0.attn_out, g0.token_adapter, g0.rank, g0.scale, g0.lora_tables,
+                                     [dict(r0.pj("o"), w_base=wq["o"])], n_tokens=T, d_in=qd, n_adapters=r0.n_ad,
+                                     max_rank=r0.max_rank, stream=st)
+        tms = {}
+        for nm, f in (("lora_qkv", qkv_b), ("lora_o", o_b)):
+            f(s_comp)
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(s_comp)
+            for _ in range(3):
+                f(s_comp)
+            e1.record(s_comp)
+            torch.cuda.synchronize()
+            tms[nm] = e0.elapsed_time(e1) / 3
+        gemm_flops = 2.0 * T * sum(step.proj[n].d_in * step.proj[n].d_out for n in cfg.projections)
+        gemm_ms = tms["lora_qkv"] + tms["lora_o"] - stage_ms["lora_qkv"] - stage_ms["lora_o"]
+        base_info = {"lora_qkv_ms": round(tms["lora_qkv"], 4), "lora_o_ms": round(tms["lora_o"], 4),
+                     "gemm_flops": int(gemm_flops), "gemm_ms": round(gemm_ms, 4),
+                     "gemm_TFLOPps": round(gemm_flops / (gemm_ms * 1e9), 1),
+                     "gemm_frac_of_mfma_peak": round(gemm_flops / (gemm_ms * 1e9) / MFMA_PEAK_TFLOPS, 4),
+                     "compute_only_tokens_per_s": round(T / ((sum(v for k, v in stage_ms.items() if k != "swap")
+                                                              + gemm_ms) * 1e-3), 1)}
+
     compute_ms = sum(v for k, v in stage_ms.items() if k != "swap")
     out = {
         "metric": "tokens/s of paged multi-LoRA layer step",
@@ -289,6 +327,7 @@ def main():
         "serialised": {"ms_per_step": round(serial_ms, 4), "tokens_per_s": round(T / (serial_ms * 1e-3), 1),
                        "compute_only_ms": round(compute_ms, 4),
                        "compute_only_tokens_per_s": round(T / (compute_ms * 1e-3), 1)},
+        "with_base_gemm": base_info,
     }
 
     if not args.no_cpu_baseline:

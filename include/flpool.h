@@ -167,7 +167,8 @@ typedef struct {
   int32_t reserved;
   int64_t ld_y;                   /* elements between rows of y (>= d_out)                    */
   void*          y;               /* device [T, ld_y], pool dtype, in/out                     */
-  const void*    w_base;          /* device [d_in, d_out] or NULL (y already holds the base)  */
+  const void*    w_base;          /* device [d_in, d_out] row-major, pool dtype, or NULL (y already
+                                     holds the base); 16-bit pools need d_in % 64 == 0           */
   const int32_t* a_tab_off;       /* device int32[n_adapters]                                 */
   const int32_t* a_row_base;      /* device int32[n_adapters]                                 */
   const int32_t* b_tab_off;       /* device int32[n_adapters]                                 */

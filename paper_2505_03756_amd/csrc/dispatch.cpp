@@ -267,9 +267,10 @@ extern "C" flp_status flp_lora_apply_paged(flp_pool* p, const flp_lora_batch* b,
       flp_set_error("flp_lora_apply_paged: projection %d has bad sizes or null/misaligned pointers", q);
       return FLP_EINVAL;
     }
-    if (pr.w_base) {
-      flp_set_error("flp_lora_apply_paged: w_base is not supported yet; put x.W_base into y and pass NULL");
-      return FLP_ENOTSUP;
+    if (pr.w_base && (!aligned16(pr.w_base) || (p->elem_bytes == 2 && b->d_in % 64))) {
+      flp_set_error("flp_lora_apply_paged: projection %d: w_base misaligned, or d_in %d not a multiple of 64", q,
+                    b->d_in);
+      return pr.w_base && aligned16(pr.w_base) ? FLP_ENOTSUP : FLP_EINVAL;
     }
   }
   std::lock_guard<std::mutex> lk(p->mu);
@@ -308,11 +309,23 @@ extern "C" flp_status flp_lora_apply_paged(flp_pool* p, const flp_lora_batch* b,
     const int rp = 16 * nt;
     v_elems = (size_t)ks * c.v_rows * b->n_proj * rp;
   }
+  size_t wt_bytes = 0;                         // transposed copy of the widest dense base matrix
+  if (p->elem_bytes == 2)
+    for (int q = 0; q < b->n_proj; ++q)
+      if (b->proj[q].w_base) wt_bytes = std::max(wt_bytes, (size_t)b->d_in * b->proj[q].d_out * 2);
+  wt_bytes = (wt_bytes + 255) & ~(size_t)255;
+  size_t base_bytes[FLP_MAX_PROJ] = {0, 0, 0, 0}, base_total = 0;   // unrounded base terms (16-bit pools)
+  if (p->elem_bytes == 2)
+    for (int q = 0; q < b->n_proj; ++q)
+      if (b->proj[q].w_base) {
+        base_bytes[q] = (T * b->proj[q].d_out * 4 + 255) & ~(size_t)255;
+        base_total += base_bytes[q];
+      }
   const size_t v_bytes = (v_elems * 4 + 255) & ~(size_t)255;
   const size_t seg_bytes = ((size_t)(4 * b->n_adapters + 5) * 4 + 255) & ~(size_t)255;
   const size_t perm_bytes = (T * 4 + 255) & ~(size_t)255;
   void* ws = nullptr;
-  FLP_TRY(flp_workspace(p, v_bytes + seg_bytes + perm_bytes, &ws));
+  FLP_TRY(flp_workspace(p, v_bytes + seg_bytes + perm_bytes + wt_bytes + base_total, &ws));
   FlpLoraArgs a{};
   a.pool = p->dev_base;
   a.block_elems = p->block_elems;
@@ -336,6 +349,21 @@ extern "C" flp_status flp_lora_apply_paged(flp_pool* p, const flp_lora_batch* b,
   a.tile_start = a.seg_start + b->n_adapters + 1;
   a.group_start = a.tile_start + b->n_adapters + 1;
   a.perm = (int32_t*)(w + v_bytes + seg_bytes);
+  // base term first where the caller asked for it (x . W_base), then the adapters' deltas on top.
+  // 16-bit pools also keep the product unrounded in the workspace so that base + delta is rounded
+  // once; tokens without an adapter keep the rounded value that the GEMM wrote into y.
+  {
+    uint8_t* wt = w + v_bytes + seg_bytes + perm_bytes;
+    uint8_t* basep = wt + wt_bytes;
+    for (int q = 0; q < b->n_proj; ++q) {
+      if (!b->proj[q].w_base) continue;
+      float* y32 = p->elem_bytes == 2 ? (float*)basep : nullptr;
+      FLP_TRY(flp_launch_base_gemm(p->cfg.dtype, b->x, b->ld_x, b->proj[q].w_base, b->proj[q].y, b->proj[q].ld_y,
+                                   b->n_tokens, b->proj[q].d_out, b->d_in, wt, y32, stream));
+      a.base32[q] = y32;
+      basep += base_bytes[q];
+    }
+  }
   if (!mfma_ok) return flp_launch_lora_simple(p->cfg.dtype, a, stream);
   FLP_TRY(flp_launch_lora_segment(a.T, a.token_adapter, a.n_adapters, a.n_seg, a.seg_adapter, a.seg_start, a.perm,
                                   16 * c.mt, a.tile_start, c.group_tokens, a.group_start, stream));

@@ -128,6 +128,9 @@ struct FlpLoraArgs {
   const float* scale;
   const int32_t* tables;
   flp_lora_proj proj[FLP_MAX_PROJ];
+  // unrounded base term x.W_base [T, d_out] of a projection whose w_base was given (16-bit pools), else null:
+  // the expand kernels then take the base from here instead of y and round base + delta once
+  const float* base32[FLP_MAX_PROJ];
   // workspace
   float* v;                    // [T, n_proj, max_rank] fp32
   int32_t* n_seg;
@@ -153,3 +156,5 @@ flp_status flp_launch_lora_segment(int32_t T, const int32_t* token_adapter, int3
                                    int32_t* tile_start, int32_t tg, int32_t* group_start, hipStream_t stream);
 flp_status flp_launch_lora_mfma(int dtype, const FlpLoraArgs& a, const FlpLoraMfma& c, hipStream_t stream);
 flp_status flp_launch_lora_simple(int dtype, const FlpLoraArgs& a, hipStream_t stream);
+flp_status flp_launch_base_gemm(int dtype, const void* x, int64_t ld_x, const void* w, void* y, int64_t ld_y, int M,
+                                int N, int K, void* wt_scratch, float* y32, hipStream_t stream);

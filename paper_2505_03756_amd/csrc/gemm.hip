@@ -1,0 +1,204 @@
+// Base projection y = x . W_base for flp_lora_apply_paged when the caller passes w_base
+// (paper Eq. 1: W' = W + A B; this is the W term.  The paper keeps the base model outside the
+// pool, and so does this library: w_base is an ordinary dense [d_in, d_out] matrix).
+//
+// 16-bit pools: W is first transposed into the pool's workspace ([d_out, d_in], so that both
+// operands are contiguous along the contraction), then a tiled MFMA GEMM runs: 128 x 128 output
+// tile per workgroup (4 waves, 64 x 64 each, mfma_f32_32x32x16), 64-deep k tiles staged through
+// LDS (XOR-swizzled 16-byte chunks, double buffered, next tile prefetched through registers).
+// The product is computed transposed (A operand = rows of W^T, B operand = token rows) and the
+// rows of W^T are fed in a permuted order so that a lane ends up with 16 consecutive output
+// columns of one token: y is written in 32-byte pieces.
+// fp32 pools: a plain one-thread-per-output kernel (the fp32 workload is tiny).
+#include <hip/hip_runtime.h>
+
+#include "flp_internal.h"
+#include "flp_types.h"
+
+namespace {
+
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef _Float16 h16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 b16x8 __attribute__((ext_vector_type(8)));
+
+struct GF16 {
+  typedef h16x8 vec;
+  static __device__ __forceinline__ f32x16 mfma(vec a, vec b, f32x16 c) {
+    return __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, c, 0, 0, 0);
+  }
+  static __device__ __forceinline__ uint16_t out(float f) { return F16::from_float(f); }
+};
+struct GBF16 {
+  typedef b16x8 vec;
+  static __device__ __forceinline__ f32x16 mfma(vec a, vec b, f32x16 c) {
+    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+  }
+  static __device__ __forceinline__ uint16_t out(float f) { return BF16::from_float(f); }
+};
+
+// ---- W [K, N] -> Wt [N, K], 16-bit elements, 64 x 64 tiles through LDS
+__global__ __launch_bounds__(256) void transpose16_kernel(const uint16_t* __restrict__ w, uint16_t* __restrict__ wt,
+                                                          int K, int N) {
+  __shared__ uint16_t tile[64][66];
+  const int k0 = blockIdx.y * 64, n0 = blockIdx.x * 64;
+  for (int i = threadIdx.x; i < 64 * 64; i += 256) {
+    const int r = i >> 6, c = i & 63;
+    tile[r][c] = (k0 + r < K && n0 + c < N) ? w[(int64_t)(k0 + r) * N + n0 + c] : (uint16_t)0;
+  }
+  __syncthreads();
+  for (int i = threadIdx.x; i < 64 * 64; i += 256) {
+    const int r = i >> 6, c = i & 63;      // r: n within tile, c: k within tile
+    if (n0 + r < N && k0 + c < K) wt[(int64_t)(n0 + r) * K + k0 + c] = tile[c][r];
+  }
+}
+
+constexpr int BM = 128, BN = 128, BK = 64;
+constexpr int kTile = 128 * BK * 2;        // bytes of one operand tile (16 KiB)
+
+// byte offset of 16-byte chunk c (0..7) of row r (0..127) inside an operand tile: two rows share
+// a 256-byte line and the 16 chunk slots of the line are XOR-swizzled with the line index, so the
+// 16 lanes that read one logical chunk of 16 consecutive rows hit 16 different bank groups
+__device__ __forceinline__ int tile_off(int r, int c) { return (r >> 1) * 256 + (((((r & 1) << 3) | c) ^ ((r >> 1) & 15)) << 4); }
+
+// The product is stored rounded into y and, when y32 is given, also unrounded as fp32 ([M, N]
+// dense): the LoRA expand kernel adds the adapter's delta to the unrounded value and rounds once;
+// rows of tokens without an adapter keep the rounded value.
+template <typename G>
+__global__ __launch_bounds__(256, 2) void gemm_nt_kernel(const uint16_t* __restrict__ x, int64_t ld_x,
+                                                         const uint16_t* __restrict__ wt, uint16_t* __restrict__ y,
+                                                         int64_t ld_y, float* __restrict__ y32, int M, int N, int K) {
+  typedef typename G::vec vec;
+  __shared__ __attribute__((aligned(16))) uint8_t smem[2][2 * kTile];      // [buffer][Wt tile | x tile]
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, lr = lane & 31, hf = lane >> 5;
+  const int n0 = blockIdx.x * BN, m0 = blockIdx.y * BM;
+  const int wn = (wave & 1) * 64, wm = (wave >> 1) * 64;                   // this wave's 64 x 64 corner
+
+  // staging: thread -> chunk (tid & 7) of rows (tid >> 3) + 32*i, i = 0..3, for both operands
+  const int sc = tid & 7, sr = tid >> 3;
+  u32x4 areg[4], breg[4];
+  auto load_tiles = [&](int k0) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int r = sr + 32 * i;
+      const int n = n0 + r < N ? n0 + r : N - 1;                            // clamped rows are never stored
+      const int m = m0 + r < M ? m0 + r : M - 1;
+      areg[i] = *reinterpret_cast<const u32x4*>(wt + (int64_t)n * K + k0 + 8 * sc);
+      breg[i] = *reinterpret_cast<const u32x4*>(x + (int64_t)m * ld_x + k0 + 8 * sc);
+    }
+  };
+  auto store_tiles = [&](uint8_t* buf) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int r = sr + 32 * i;
+      *reinterpret_cast<u32x4*>(buf + tile_off(r, sc)) = areg[i];
+      *reinterpret_cast<u32x4*>(buf + kTile + tile_off(r, sc)) = breg[i];
+    }
+  };
+
+  f32x16 acc[2][2];
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+
+  // A-operand row a of a 32-row tile is output column 16*((a>>2)&1) + 4*(a>>3) + (a&3) of that tile
+  const int acol = (((lr >> 2) & 1) << 4) | ((lr >> 3) << 2) | (lr & 3);
+
+  const int nk = K / BK;
+  load_tiles(0);
+  store_tiles(smem[0]);
+  __syncthreads();
+  for (int kt = 0; kt < nk; ++kt) {
+    const uint8_t* buf = smem[kt & 1];
+    if (kt + 1 < nk) load_tiles((kt + 1) * BK);
+#pragma unroll
+    for (int kk = 0; kk < BK / 16; ++kk) {
+      vec af[2], bf[2];
+#pragma unroll
+      for (int i = 0; i < 2; ++i) {
+        af[i] = *reinterpret_cast<const vec*>(buf + tile_off(wn + 32 * i + acol, 2 * kk + hf));
+        bf[i] = *reinterpret_cast<const vec*>(buf + kTile + tile_off(wm + 32 * i + lr, 2 * kk + hf));
+      }
+#pragma unroll
+      for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j) acc[i][j] = G::mfma(af[i], bf[j], acc[i][j]);
+    }
+    if (kt + 1 < nk) store_tiles(smem[(kt + 1) & 1]);
+    __syncthreads();
+  }
+
+  // lane (token lr of tile j, half hf) holds columns 16*hf .. 16*hf+15 of column tile i:
+  // register 4*q + r of the accumulator is column 16*hf + 4*q + r
+#pragma unroll
+  for (int j = 0; j < 2; ++j) {
+    const int m = m0 + wm + 32 * j + lr;
+    if (m >= M) continue;
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      const int n = n0 + wn + 32 * i + 16 * hf;
+      if (y32) {
+        float* yp32 = y32 + (int64_t)m * N + n;
+#pragma unroll
+        for (int e = 0; e < 16; ++e)
+          if (n + e < N) yp32[e] = acc[i][j][e];
+      }
+      uint16_t o[16];
+#pragma unroll
+      for (int e = 0; e < 16; ++e) o[e] = G::out(acc[i][j][e]);
+      uint16_t* yp = y + (int64_t)m * ld_y + n;
+      if (n + 16 <= N) {
+        u32x4 raw[2];
+        __builtin_memcpy(raw, o, 32);
+        reinterpret_cast<u32x4*>(yp)[0] = raw[0];
+        reinterpret_cast<u32x4*>(yp)[1] = raw[1];
+      } else {
+        for (int e = 0; e < 16; ++e)
+          if (n + e < N) yp[e] = o[e];
+      }
+    }
+  }
+}
+
+__global__ __launch_bounds__(256) void gemm_f32_kernel(const float* __restrict__ x, int64_t ld_x,
+                                                       const float* __restrict__ w, float* __restrict__ y,
+                                                       int64_t ld_y, int M, int N, int K) {
+  const int n = blockIdx.x * 256 + threadIdx.x, m = blockIdx.y;
+  if (n >= N) return;
+  float acc = 0.f;
+  for (int k = 0; k < K; ++k) acc = fmaf(x[(int64_t)m * ld_x + k], w[(int64_t)k * N + n], acc);
+  y[(int64_t)m * ld_y + n] = acc;
+}
+
+}  // namespace
+
+// y[M, N] = x[M, K] . w[K, N].  `wt_scratch` (16-bit types only) must hold N*K elements; `y32`
+// (16-bit types, optional) receives the unrounded product as dense fp32 [M, N].
+flp_status flp_launch_base_gemm(int dtype, const void* x, int64_t ld_x, const void* w, void* y, int64_t ld_y, int M,
+                                int N, int K, void* wt_scratch, float* y32, hipStream_t stream) {
+  if (M <= 0 || N <= 0 || K <= 0) return FLP_OK;
+  if (dtype == FLP_F32) {
+    hipLaunchKernelGGL(gemm_f32_kernel, dim3((N + 255) / 256, M), dim3(256), 0, stream, (const float*)x, ld_x,
+                       (const float*)w, (float*)y, ld_y, M, N, K);
+    FLP_TRY_HIP(hipGetLastError());
+    return FLP_OK;
+  }
+  if (K % BK != 0) {
+    flp_set_error("base GEMM: d_in %d is not a multiple of %d", K, BK);
+    return FLP_ENOTSUP;
+  }
+  hipLaunchKernelGGL(transpose16_kernel, dim3((N + 63) / 64, (K + 63) / 64), dim3(256), 0, stream, (const uint16_t*)w,
+                     (uint16_t*)wt_scratch, K, N);
+  dim3 grid((N + BN - 1) / BN, (M + BM - 1) / BM);
+  const uint16_t* xs = (const uint16_t*)x;
+  const uint16_t* ws = (const uint16_t*)wt_scratch;
+  if (dtype == FLP_F16)
+    hipLaunchKernelGGL(gemm_nt_kernel<GF16>, grid, dim3(256), 0, stream, xs, ld_x, ws, (uint16_t*)y, ld_y, y32, M, N, K);
+  else
+    hipLaunchKernelGGL(gemm_nt_kernel<GBF16>, grid, dim3(256), 0, stream, xs, ld_x, ws, (uint16_t*)y, ld_y, y32, M, N,
+                       K);
+  FLP_TRY_HIP(hipGetLastError());
+  return FLP_OK;
+}

@@ -281,10 +281,17 @@ __global__ __launch_bounds__(256) void lora_expand_rows_kernel(FlpLoraArgs a) {
   }
   ST* yp = reinterpret_cast<ST*>(pr.y) + (int64_t)t * pr.ld_y + col0;
   ST ys[EPL];
-  u32x4 raw = *reinterpret_cast<const u32x4*>(yp);
-  __builtin_memcpy(ys, &raw, 16);
+  u32x4 raw;
+  if (a.base32[p]) {                               // unrounded base from the dense projection
+    const float* bp = a.base32[p] + (int64_t)t * pr.d_out + col0;
 #pragma unroll
-  for (int e = 0; e < EPL; ++e) ys[e] = S::from_float(fmaf(sc, acc[e], S::to_float(ys[e])));
+    for (int e = 0; e < EPL; ++e) ys[e] = S::from_float(fmaf(sc, acc[e], bp[e]));
+  } else {
+    raw = *reinterpret_cast<const u32x4*>(yp);
+    __builtin_memcpy(ys, &raw, 16);
+#pragma unroll
+    for (int e = 0; e < EPL; ++e) ys[e] = S::from_float(fmaf(sc, acc[e], S::to_float(ys[e])));
+  }
   __builtin_memcpy(&raw, ys, 16);
   *reinterpret_cast<u32x4*>(yp) = raw;
 }

@@ -242,12 +242,13 @@ __global__ __launch_bounds__(64) void lora_expand_mfma_kernel(FlpLoraArgs a, Flp
       const int pos = pos_t + n;
       const bool tvalid = pos < pos_stop;
       uint16_t* yrow = reinterpret_cast<uint16_t*>(pr.y) + (int64_t)tok * pr.ld_y + col_begin + 16 * kg;
+      const float* brow = a.base32[p] ? a.base32[p] + (int64_t)tok * pr.d_out + col_begin + 16 * kg : nullptr;
       // the y pieces are requested first so that their latency overlaps the preparation of v;
       // the next sub-tile's token index is fetched now as well
       u32x4 yraw[C64][2];
 #pragma unroll
       for (int ch = 0; ch < C64; ++ch)
-        if (col_begin + 64 * ch < pr.d_out) {
+        if (col_begin + 64 * ch < pr.d_out && !brow) {
           yraw[ch][0] = *reinterpret_cast<const u32x4*>(yrow + 64 * ch);
           yraw[ch][1] = *reinterpret_cast<const u32x4*>(yrow + 64 * ch + 8);
         }
@@ -296,11 +297,21 @@ __global__ __launch_bounds__(64) void lora_expand_mfma_kernel(FlpLoraArgs a, Flp
           }
           if (tvalid) {
             uint16_t ys[16];
-            __builtin_memcpy(ys, &yraw[ch][0], 32);
+            if (brow) {                          // unrounded base from the dense projection
 #pragma unroll
-            for (int tau = 0; tau < 4; ++tau)
+              for (int tau = 0; tau < 4; ++tau) {
+                const f32x4 b4 = *reinterpret_cast<const f32x4*>(brow + 64 * ch + 4 * tau);
 #pragma unroll
-              for (int i = 0; i < 4; ++i) ys[4 * tau + i] = S::from_float(S::to_float(ys[4 * tau + i]) + acc[tau][i]);
+                for (int i = 0; i < 4; ++i) ys[4 * tau + i] = S::from_float(b4[i] + acc[tau][i]);
+              }
+            } else {
+              __builtin_memcpy(ys, &yraw[ch][0], 32);
+#pragma unroll
+              for (int tau = 0; tau < 4; ++tau)
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+                  ys[4 * tau + i] = S::from_float(S::to_float(ys[4 * tau + i]) + acc[tau][i]);
+            }
             u32x4 raw[2];
             __builtin_memcpy(raw, ys, 32);
             *reinterpret_cast<u32x4*>(yrow + 64 * ch) = raw[0];

@@ -104,11 +104,15 @@ class GpuStep:
         self.torch.cuda.synchronize()
         return to_np(self.host, self.sd)
 
-    def lora(self, names, x_key="x"):
-        """Run flp_lora_apply_paged for the named projections on copies of the base terms; returns storage arrays."""
+    def lora(self, names, x_key="x", w_base=None):
+        """Run flp_lora_apply_paged for the named projections on copies of the base terms; returns storage arrays.
+        `w_base`: optional dict name -> device tensor [d_in, d_out]; y then starts as garbage and is overwritten."""
         st = self.step
         ys = {n: self.acts["base_" + n].clone() for n in names}
         projs = [dict(y=ys[n], d_out=st.proj[n].d_out, **self.proj[n]) for n in names]
+        if w_base:
+            for pj, n in zip(projs, names):
+                pj["w_base"] = w_base[n]
         x = self.acts[x_key]
         self.pool.lora_apply_paged(x, self.token_adapter, self.rank, self.scale, self.lora_tables, projs,
                                    n_tokens=st.n_tokens, d_in=x.shape[1], n_adapters=len(st.rank),

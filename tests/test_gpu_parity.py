@@ -167,6 +167,30 @@ def test_lora_matrix_core_shapes(name):
         assert err.max() <= ulp * (np.abs(want).max() + 1.0), (n, err.max())
 
 
+@pytest.mark.parametrize("name", ["tiny", "f16_prefill", "bf16_gqa_mixed", "f16_long_segments"])
+def test_lora_with_dense_base(name):
+    """w_base given: y = x.W_base + delta, the library computes the base term itself (Eq. 1's W)."""
+    cfg = (CASES.get(name) or LORA_CASES[name])()
+    step = wl.make_step(cfg)
+    rng = np.random.default_rng(55)
+    dev0 = resident_pool(step)
+    g = GpuStep(step, dev0, np.zeros((1, cfg.block_elems), dev0.dtype))
+    rtol, atol = TOL[cfg.dtype]
+    names = [p for p in cfg.projections if p in ("q", "k", "v")]
+    W = {n: wl.quantize((rng.standard_normal((cfg.hidden, step.proj[n].d_out)) / np.sqrt(cfg.hidden)).astype(np.float32),
+                        cfg.dtype) for n in names}
+    got = g.lora(names, w_base={n: to_dev(W[n]) for n in names})
+    sel = np.sort(rng.choice(step.n_tokens, size=min(step.n_tokens, 64), replace=False)).astype(np.int32)
+    for n in names:
+        pr = step.proj[n]
+        want = oracle.lora_apply(dev0, cfg.dtype, step.acts["x"], step.token_adapter, step.rank, step.scale,
+                                 pr.a_tab_off, pr.a_row_base, pr.b_tab_off, pr.b_row_base, step.lora_tables,
+                                 pr.d_out, w_base=W[n], sel=sel)
+        ok, worst, nbad = close(wl.dequantize(got[n][sel], cfg.dtype), want, rtol, atol)
+        assert ok, "%s: max err %g, %d elements out of tolerance" % (n, worst, nbad)
+        assert np.abs(want).max() > 1.0          # the base term is really there
+
+
 def test_segmentation_bit_exact():
     import torch
     rng = np.random.default_rng(9)
