@@ -24,7 +24,6 @@ import time
 
 ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
-sys.path.insert(0, os.path.join(ROOT, "tests"))
 
 HBM_PEAK_GBS = 8000.0        # MI355X HBM3E, published
 # HBM bytes per launch of the dominant kernel, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this
@@ -61,7 +60,7 @@ def main():
 
     import numpy as np
     import torch
-    from helpers import GpuStep, to_dev
+    from paper_2505_03756_amd.harness import GpuStep, to_dev
     from paper_2505_03756_amd import flpool
     from paper_2505_03756_amd import workload as wl
 
@@ -341,7 +340,7 @@ def cpu_baseline(step, target_s):
     its attention row over the full context)."""
     import numpy as np
     import oracle
-    from helpers import resident_pool
+    from paper_2505_03756_amd.harness import resident_pool
     cfg = step.cfg
     pool = resident_pool(step)
     bt, n_kv, d, n_h = cfg.block_tokens, cfg.n_kv_heads, cfg.head_dim, cfg.n_q_heads
