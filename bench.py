@@ -27,7 +27,7 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0        # MI355X HBM3E, published
 # HBM bytes per launch of the dominant kernel, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this
-# file (profiles/attn_mfma_7b_prefill_pmc.md), scaled by what the same counters read for a plain
+# file (profiles/bench_7b_prefill_pmc.md), scaled by what the same counters read for a plain
 # device-to-device copy of 1 GiB (FETCH_SIZE reads half the bytes, WRITE_SIZE all of them).  Only
 # valid for the default workload and seed; null otherwise.
 MEASURED_TRAFFIC = {("7b_prefill", 20250504): 1.603e9, ("7b_decode", 20250505): None}

@@ -83,8 +83,7 @@ flp_status flp_launch_copy_blocks(const uint8_t* src_base, uint8_t* dst_base, co
   // 55 GB/s out), and every further workgroup that waits on host-link reads slows the HBM
   // traffic of the kernels running beside the swap (96 workgroups: a streaming copy on another
   // stream runs 4x slower; 16: 1.1x); a tier that lives in device memory wants the whole chip
-  static const int tune = [] { const char* e = getenv("FLP_SWAP_WGS"); return e ? atoi(e) : 0; }();
-  const int64_t max_wgs = tune > 0 ? tune : (over_host_link ? 16 : 2048);
+  const int64_t max_wgs = over_host_link ? 16 : 2048;
   dim3 grid((unsigned)(total < max_wgs ? total : max_wgs));
   if (block_bytes % 16 == 0) {
     hipLaunchKernelGGL(copy_blocks_kernel<u32x4>, grid, dim3(kThreads), 0, stream, src_base, dst_base, src_ids_dev,
