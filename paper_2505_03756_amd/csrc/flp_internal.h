@@ -149,6 +149,7 @@ struct FlpLoraMfma {
   int32_t tiles_bound;         // host-side upper bound of the number of tiles
   int32_t group_tokens;        // tokens per tile group of the expand kernel (multiple of 16*mt)
   int32_t groups_bound;
+  int32_t slabs;               // column slabs per projection (set by the launcher)
 };
 
 flp_status flp_launch_lora_segment(int32_t T, const int32_t* token_adapter, int32_t n_adapters, int32_t* n_seg,

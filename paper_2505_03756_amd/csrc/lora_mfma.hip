@@ -76,7 +76,11 @@ template <typename L, int MT, int NT>
 __global__ __launch_bounds__(256) void lora_shrink_mfma_kernel(FlpLoraArgs a, FlpLoraMfma c) {
   typedef typename L::vec vec;
   extern __shared__ float red[];                       // [4 waves][n_acc][64 lanes]
-  const int tile = blockIdx.x, ks = blockIdx.y;
+  // Each XCD (workgroups are placed on the 8 XCDs round-robin by their linear id) takes a contiguous
+  // eighth of the tiles with all their k splits: tiles of one adapter are neighbours, so its A pages
+  // are fetched into one L2 instead of eight.
+  const int per_xcd = (c.tiles_bound + 7) / 8;
+  const int tile = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3) / c.k_splits, ks = (blockIdx.x >> 3) % c.k_splits;
   const int n_seg = *a.n_seg;
   if (tile >= a.tile_start[n_seg]) return;
   const int s = find_segment(a.tile_start, n_seg, tile);
@@ -178,7 +182,12 @@ __global__ __launch_bounds__(64) void lora_expand_mfma_kernel(FlpLoraArgs a, Flp
   typedef typename L::elem elem;
   typedef typename L::S S;
   constexpr int CH = 8 / NT;                          // 32-column chunks per resident piece
-  const int group = blockIdx.x, slab = blockIdx.y, p = blockIdx.z;
+  // All column slabs and projections of one tile group run on one XCD (workgroups are placed on the
+  // 8 XCDs round-robin by their linear id): they re-read the same rows of v and the same B pages,
+  // which then stay in that XCD's L2.
+  const int per_group = c.slabs * a.n_proj;
+  const int xcd = blockIdx.x & 7, q = blockIdx.x >> 3;
+  const int group = (q / per_group) * 8 + xcd, slab = (q % per_group) / a.n_proj, p = (q % per_group) % a.n_proj;
   const int n_seg = *a.n_seg;
   if (group >= a.group_start[n_seg]) return;
   const flp_lora_proj& pr = a.proj[p];
@@ -333,14 +342,19 @@ flp_status launch_pair(const FlpLoraArgs& a, const FlpLoraMfma& c, hipStream_t s
                                     hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));
     attr_set = true;
   }
-  hipLaunchKernelGGL((lora_shrink_mfma_kernel<L, MT, NT>), dim3(c.tiles_bound, c.k_splits), dim3(256), smem, stream, a,
-                     c);
+  hipLaunchKernelGGL((lora_shrink_mfma_kernel<L, MT, NT>), dim3((unsigned)((c.tiles_bound + 7) / 8 * 8 * c.k_splits)),
+                     dim3(256), smem, stream, a, c);
   FLP_TRY_HIP(hipGetLastError());
   int max_dout = 0;
   for (int p = 0; p < a.n_proj; ++p) max_dout = a.proj[p].d_out > max_dout ? a.proj[p].d_out : max_dout;
-  const unsigned slabs = (unsigned)((max_dout + c.cols_per_slab - 1) / c.cols_per_slab);
-  hipLaunchKernelGGL((lora_expand_mfma_kernel<L, NT>), dim3(c.groups_bound, slabs, a.n_proj), dim3(64), 0, stream, a,
-                     c);
+  FlpLoraMfma ce = c;
+  ce.slabs = (max_dout + c.cols_per_slab - 1) / c.cols_per_slab;
+  const int64_t n_wg = (int64_t)((c.groups_bound + 7) / 8) * 8 * ce.slabs * a.n_proj;
+  if (n_wg > INT32_MAX) {
+    flp_set_error("LoRA (matrix-core path): %lld workgroups, too many for one launch", (long long)n_wg);
+    return FLP_ENOTSUP;
+  }
+  hipLaunchKernelGGL((lora_expand_mfma_kernel<L, NT>), dim3((unsigned)n_wg), dim3(64), 0, stream, a, ce);
   FLP_TRY_HIP(hipGetLastError());
   return FLP_OK;
 }
