@@ -1,0 +1,209 @@
+"""The library's cache manager / cache swapper (include/flcache.h) against the oracle: the same seeded
+traces of add / match / insert / release / tick must produce the same block lists, in the same order,
+and the same tree.  Host logic only: runs without a GPU on a pool over caller-owned host memory."""
+import ctypes as C
+import os
+import re
+import time
+
+import numpy as np
+import pytest
+
+from oracle.cache_oracle import HBM, CacheOracle
+from paper_2505_03756_amd import flcache, flpool
+from tests.cache_trace import run_trace
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+BLOCK_BYTES = 2 * 4 * 1 * 64 * 2          # bt = 4, one kv head of 64 channels, 16 bit
+
+
+def host_pool(n_dev, n_host, bt):
+    be = 2 * bt * 1 * 64
+    dev = np.zeros(n_dev * be + 256, np.uint16)
+    host = np.zeros(n_host * be + 256, np.uint16)
+    al = lambda a: (a.ctypes.data + 255) & ~255
+    p = flpool.Pool("f16", 1, 64, n_dev, n_host, block_tokens=bt, dev=al(dev), host=al(host))
+    p._bufs = (dev, host)
+    return p
+
+
+class LibDriver:
+    """The binding behind the interface of tests/cache_trace.py."""
+
+    def __init__(self, n_dev, n_host, bt, **cfg):
+        self.pool = host_pool(n_dev, n_host, bt)
+        self.c = flcache.Cache(self.pool, block_tokens=bt, **cfg)
+        self.upper = cfg.get("upper", 0.95)
+
+    def add_lora(self, lora_id, n_blocks, tier, now):
+        try:
+            return [int(i) for i in self.c.add_lora(lora_id, n_blocks, tier, now)]
+        except flpool.FlpError as e:
+            assert e.code == flpool.FLP_ENOSPC
+            return None
+
+    def match(self, lora_id, tokens, now):
+        q, lb, kv, sh, sd = self.c.match(lora_id, tokens, now)
+        return (q, None if lb is None else [int(i) for i in lb], [int(i) for i in kv],
+                list(zip([int(i) for i in sh], [int(i) for i in sd])))
+
+    def insert(self, q, tokens, new, now):
+        return [int(i) for i in self.c.insert(q, tokens, new, now)]
+
+    def release(self, q):
+        self.c.release(q)
+
+    def tick(self, now, bs):
+        (od, oh), (ih, idv), dr = self.c.tick(now, bs)
+        return (list(zip([int(i) for i in od], [int(i) for i in oh])),
+                list(zip([int(i) for i in ih], [int(i) for i in idv])), [int(i) for i in dr])
+
+    def alloc_dev(self, n):
+        try:
+            return [int(i) for i in self.pool.alloc(n, 0)]
+        except flpool.FlpError:
+            return None
+
+    def free_dev(self, ids):
+        self.pool.free(np.asarray(ids, np.int32), 0)
+
+    def usage(self):
+        return self.c.stats()["usage"]
+
+    def snapshot(self):
+        # (id, kind, parent, tier, blocks..., visits, last use, pins) with the oracle's field order
+        return [(i, k, p, t, fb, nb, v, lu, pins) for i, k, p, t, fb, nb, v, lu, pins in self.c.snapshot()]
+
+
+class OracleDriver(CacheOracle):
+    def alloc_dev(self, n):
+        return self.free[HBM].alloc(n)
+
+    def free_dev(self, ids):
+        self.free[HBM].free(ids)
+
+    def snapshot(self):
+        return [(i, k, p, t, b[0] if b else -1, len(b), v, lu, pins) for i, k, p, t, b, v, lu, pins in super().snapshot()]
+
+
+def make_oracle(n_dev, n_host, bt, **cfg):
+    return OracleDriver(n_dev, n_host, block_tokens=bt, block_bytes=BLOCK_BYTES, **cfg)
+
+
+VARIANTS = [dict(), dict(use_lru=True), dict(ignore_dependencies=True), dict(no_lora_reward=True),
+            dict(upper=0.6, lower=0.3, time_scale_s=3.0), dict(pcie_bytes_per_s=1e6, time_scale_s=0.5)]
+
+
+def test_library_exports_every_declared_symbol():
+    lib = flpool.load()
+    header = open(os.path.join(ROOT, "include", "flcache.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b(flc_[a-z_0-9]+)\s*\(", header))
+    assert declared == set(flcache.EXPORTS)
+    for name in declared:
+        assert hasattr(lib, name), name
+    assert C.sizeof(flcache.Config) == 16 + 4 * 8
+    assert C.sizeof(flcache.Stats) == 10 * 8
+    assert C.sizeof(flcache.NodeInfo) == 8 * 4 + 16
+
+
+@pytest.mark.parametrize("variant", range(len(VARIANTS)))
+@pytest.mark.parametrize("seed", [0, 1, 2, 3])
+def test_traces_agree_with_the_oracle_block_for_block(seed, variant):
+    cfg = VARIANTS[variant]
+    _, want = run_trace(make_oracle, 1000 * variant + seed, **cfg)
+    _, got = run_trace(LibDriver, 1000 * variant + seed, **cfg)
+    assert len(want) == len(got)
+    for k, (w, g) in enumerate(zip(want, got)):
+        assert w == g, "record %d: oracle %r, library %r" % (k, w, g)
+
+
+def test_host_tier_full_forgets_victims_like_the_oracle():
+    for seed in range(4):
+        _, want = run_trace(make_oracle, 50 + seed, n_dev=64, n_host=12, n_steps=400)
+        _, got = run_trace(LibDriver, 50 + seed, n_dev=64, n_host=12, n_steps=400)
+        assert want == got
+        assert any(r[0] == "tick" and r[3] for r in want), "the trace was meant to drop nodes"
+
+
+def test_cost_model_values_agree_with_the_oracle():
+    o, _ = run_trace(make_oracle, 7, n_steps=200)
+    l, _ = run_trace(LibDriver, 7, n_steps=200)
+    for bs in (1, 4, 32):
+        assert l.c.low_lora(bs) == o.low_lora(bs)
+    now = 5000.0
+    low, nl = o.low_lora(4), o.now_lora()
+    for n in o.nodes.values():
+        if n is not o.root:
+            assert l.c.eval(n.id, now, 4) == o.eval(n, now, low, nl)
+    s = l.c.stats()
+    assert s["invalid_kv_blocks"] == o.invalid_kv_blocks() == 0
+    assert s["n_nodes"] == len(o.nodes) - 1 and s["n_lora_hbm"] == o.now_lora() and s["n_queries"] == o.n_queries
+
+
+def test_errors_leave_the_cache_unchanged():
+    d = LibDriver(32, 32, 4)
+    c = d.c
+    c.add_lora(1, 2, 0, 0.0)
+    with pytest.raises(flpool.FlpError) as e:
+        c.add_lora(1, 2, 0, 0.0)
+    assert e.value.code == flpool.FLP_EDUP
+    with pytest.raises(flpool.FlpError) as e:
+        c.add_lora(2, 100, 0, 0.0)
+    assert e.value.code == flpool.FLP_ENOSPC
+    with pytest.raises(flpool.FlpError) as e:
+        c.match(99, [1, 2, 3, 4], 0.0)
+    assert e.value.code == flpool.FLP_EINVAL
+    with pytest.raises(flpool.FlpError) as e:
+        c.release(12345)
+    assert e.value.code == flpool.FLP_EINVAL
+    q, lb, kv, sh, sd = c.match(1, list(range(8)), 1.0)
+    with pytest.raises(flpool.FlpError) as e:
+        c.insert(q, list(range(4)), [5, 6], 1.0)            # tokens do not cover two new blocks
+    assert e.value.code == flpool.FLP_EINVAL
+    with pytest.raises(flpool.FlpError) as e:
+        c.insert(q, list(range(8)), [5, 600], 1.0)          # id outside the pool
+    assert e.value.code == flpool.FLP_ERANGE
+    assert c.stats()["n_nodes"] == 1 and d.pool.num_free(0) == 30
+
+
+def test_overheads_stay_within_the_papers_budget():
+    """Section 7.8 of the paper: matching and updating below 0.5 ms, the swapping decision within 5 ms.
+    Tree of 100 LoRAs and 60 000 KV blocks (a 15 GiB pool of 256 KiB blocks), queries of 1024 tokens."""
+    bt = 16
+    n_dev, n_host = 60000, 60000
+    pool = host_pool(n_dev, n_host, bt)        # (zero pages that are never touched: only ids are used)
+    c = flcache.Cache(pool, block_tokens=bt, upper=0.95, lower=0.70)
+    rng = np.random.default_rng(0)
+    for a in range(100):
+        c.add_lora(a, 4, 0, 0.0)
+    convs = []
+    now = 0.0
+    t_match = []
+    while pool.num_free(0) > 0.03 * n_dev:
+        now += 0.01
+        a = int(rng.integers(0, 100))
+        if convs and rng.random() < 0.5:
+            base = convs[int(rng.integers(0, len(convs)))]
+            a, toks = base[0], np.concatenate([base[1], rng.integers(0, 32000, size=256)]).astype(np.int32)
+        else:
+            toks = rng.integers(0, 32000, size=1024).astype(np.int32)
+        t0 = time.perf_counter()
+        q, lb, kv, sh, sd = c.match(a, toks, now)
+        n_new = len(toks) // bt - len(kv)
+        new = pool.alloc(n_new, 0)
+        back = c.insert(q, toks, new, now)
+        c.release(q)
+        t_match.append(time.perf_counter() - t0)
+        assert len(back) == 0
+        convs.append((a, toks))
+    t0 = time.perf_counter()
+    (od, oh), (ih, idv), dr = c.tick(now + 1.0, 16, cap=65536)
+    t_tick = time.perf_counter() - t0
+    s = c.stats()
+    assert len(od) > 0 and s["usage"] <= 0.95 + 1e-9 and s["invalid_kv_blocks"] == 0
+    mean_match = sum(t_match) / len(t_match)
+    print("nodes %d: match+insert+release mean %.3f ms, max %.3f ms; tick (%d moves) %.3f ms" %
+          (s["n_nodes"], mean_match * 1e3, max(t_match) * 1e3, len(od), t_tick * 1e3))
+    assert mean_match < 0.5e-3
+    assert t_tick < 5e-3
