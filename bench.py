@@ -41,6 +41,9 @@ def parse():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=4)
     ap.add_argument("--workload", default="7b_prefill")
+    ap.add_argument("--swap-frac", type=float, default=None,
+                    help="override the share of reusable blocks that arrive over the host link each step "
+                         "(sweep for the break-even between swap and compute; the headline uses the workload's own)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample")
     ap.add_argument("--seed", type=int, default=None)
@@ -67,6 +70,8 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
     cfg = wl.config(args.workload)
+    if args.swap_frac is not None:
+        cfg = cfg.scaled(swap_in_frac=float(args.swap_frac))
     if cfg.n_dev_blocks * cfg.block_bytes > 200 * 2 ** 30:
         raise SystemExit("workload %s is a parity-test shape; this bench runs 7b_prefill or 7b_decode"
                          % args.workload)
