@@ -6,11 +6,11 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 
 
-def run_hip_probe():
-    exe = os.path.join(HERE, "_issue_power_probe")
+def run_hip_probe(name="issue_power_probe"):
+    exe = os.path.join(HERE, "_" + name)
     cmd = [os.environ.get("HIPCC", "/opt/rocm/bin/hipcc"), "--offload-arch=gfx950", "-O3", "-std=c++17",
            "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-o", exe,
-           os.path.join(HERE, "issue_power_probe.hip")]
+           os.path.join(HERE, name + ".hip")]
     r = subprocess.run(cmd, capture_output=True, text=True)
     if r.returncode != 0:
         sys.exit("hipcc failed:\n" + r.stderr)
@@ -74,5 +74,6 @@ def per_tile():
 if __name__ == "__main__":
     ap = argparse.ArgumentParser()
     ap.add_argument("--per-tile", action="store_true")
+    ap.add_argument("--hbm", action="store_true", help="rates of plain read / copy / update-in-place kernels")
     a = ap.parse_args()
-    sys.exit(per_tile() if a.per_tile else run_hip_probe())
+    sys.exit(per_tile() if a.per_tile else run_hip_probe("hbm_stream_probe") if a.hbm else run_hip_probe())
