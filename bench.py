@@ -44,6 +44,13 @@ def parse():
     ap.add_argument("--swap-frac", type=float, default=None,
                     help="override the share of reusable blocks that arrive over the host link each step "
                          "(sweep for the break-even between swap and compute; the headline uses the workload's own)")
+    ap.add_argument("--adapters", type=int, default=None, help="override the number of adapters (the paper's "
+                    "1000 / 2000 LoRA experiment, section 6.9)")
+    ap.add_argument("--adapter-dist", default=None, choices=["uniform", "zipf", "distinct", "skewed"],
+                    help="override how sequences pick their adapter (section 6.9: uniform, distinct, skewed-x)")
+    ap.add_argument("--skew-std", type=float, default=None, help="x of skewed-x, in adapter ids")
+    ap.add_argument("--seqs", type=int, default=None, help="override the number of sequences; the new-token range "
+                    "is scaled so that the step keeps its token count")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample")
     ap.add_argument("--seed", type=int, default=None)
@@ -72,6 +79,21 @@ def main():
     cfg = wl.config(args.workload)
     if args.swap_frac is not None:
         cfg = cfg.scaled(swap_in_frac=float(args.swap_frac))
+    over = {}
+    if args.adapters is not None:
+        over["n_adapters"] = int(args.adapters)
+    if args.adapter_dist is not None:
+        over["adapter_dist"] = args.adapter_dist
+    if args.skew_std is not None:
+        over["skew_std"] = float(args.skew_std)
+    if args.seqs is not None and args.seqs != cfg.n_seqs:
+        f = cfg.n_seqs / float(args.seqs)
+        over["n_seqs"] = int(args.seqs)
+        if cfg.decode_frac < 1.0:
+            over["new_range"] = (max(1, int(round(cfg.new_range[0] * f))), max(1, int(round(cfg.new_range[1] * f))))
+            over["prefix_range"] = (int(round(cfg.prefix_range[0] * f)), int(round(cfg.prefix_range[1] * f)))
+    if over:
+        cfg = cfg.scaled(**over)
     if cfg.n_dev_blocks * cfg.block_bytes > 200 * 2 ** 30:
         raise SystemExit("workload %s is a parity-test shape; this bench runs 7b_prefill or 7b_decode"
                          % args.workload)
@@ -254,7 +276,7 @@ def main():
     a = kernels["attention"]
     t_hbm = a["bytes"] / (HBM_PEAK_GBS * 1e9)
     t_mfma = a["flops"] / (MFMA_PEAK_TFLOPS * 1e12)
-    traffic = MEASURED_TRAFFIC.get((cfg.name, seed))
+    traffic = MEASURED_TRAFFIC.get((cfg.name, seed)) if not over and args.swap_frac is None else None
     kname = "attn_mfma_kernel" if (cfg.dtype != "f32" and cfg.head_dim == 128 and
                                    int(N.max()) * (n_h // n_kv) >= 8) else "attn_rows_kernel"
     if cfg.dtype != "f32" and t_mfma > t_hbm:
@@ -323,7 +345,8 @@ def main():
                    "hidden": cfg.hidden, "heads": "%dx%d (kv %d)" % (n_h, d, n_kv), "adapters": int(len(active)),
                    "ranks": sorted(set(int(r) for r in step.rank[active])),
                    "swap_in_blocks": [int(len(r.step.swap_in_dev)) for r in runners], "block_bytes": cfg.block_bytes,
-                   "base_gemm": "excluded (y arrives holding x.W)",
+                   "base_gemm": "excluded (y arrives holding x.W)", "overrides": over or None,
+                   "adapter_pool": cfg.n_adapters, "adapter_dist": cfg.adapter_dist,
                    "swap": ("own stream, overlapped with the previous batch's compute (two alternating batches)"
                             if n_sets == 2 else "none in this workload")},
         "roofline": roof,

@@ -48,9 +48,9 @@ typedef struct flc_cache flc_cache;
 
 typedef struct {
   int32_t block_tokens;        /* tokens per KV node = block_tokens of the pool (> 0)                   */
-  int32_t use_lru;             /* ablation (section 7.5): Eval_i = time of last use                     */
-  int32_t ignore_dependencies; /* ablation (section 7.4): every unused node is a candidate              */
-  int32_t no_lora_reward;      /* ablation (section 7.6): LoRA_Eval = 1                                 */
+  int32_t use_lru;             /* ablation (section 6.7): Eval_i = time of last use                     */
+  int32_t ignore_dependencies; /* ablation (section 6.6): every unused node is a candidate              */
+  int32_t no_lora_reward;      /* ablation (section 6.8): LoRA_Eval = 1                                 */
   double upper, lower;         /* HBM usage thresholds of section 5.3 (the paper uses 0.95 and 0.70)    */
   double pcie_bytes_per_s;     /* host link bandwidth behind cost_i of Eq. 5                            */
   double time_scale_s;         /* seconds per unit of t_i in Eq. 5 (the paper gives no unit)            */

@@ -23,7 +23,7 @@ What it models, in the paper's order:
   threshold; above the upper one the candidates (HBM leaves) are swapped out in increasing order
   of Eval, below the lower one the candidates (host roots) are swapped in in decreasing order,
   one by one, until the usage is back between the thresholds.
-* Sections 7.4-7.6 (ablations): LRU instead of the cost model, no dependencies (every node is
+* Sections 6.6-6.8 (ablations): LRU instead of the cost model, no dependencies (every node is
   a candidate), no LoRA reward.
 
 Readings where the paper is silent are listed in the design notes; the ones that matter here:

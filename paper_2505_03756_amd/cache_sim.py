@@ -1,7 +1,7 @@
 """Trace-driven run of the cache manager / cache swapper (include/flcache.h) on a synthetic multi-LoRA
 chat workload: host logic only, block ids only (no block contents are touched, no GPU needed).
 
-Stands in for the paper's chatbot scenario (section 6: multi-turn conversations, tens of LoRAs with
+Stands in for the paper's chatbot scenario (section 6.2: multi-turn conversations, tens of LoRAs with
 skewed popularity, about two queries per second); none of the paper's traces is reproduced.  Recipe,
 all seeded: conversations arrive as a Poisson process; each picks a LoRA by Zipf(1) over a seeded
 permutation, starts from that LoRA's shared 128-token system prompt and has a geometric number of
@@ -9,11 +9,11 @@ turns; a turn appends a prompt and a response of uniform random lengths (fresh r
 the conversation's history and is sent after an exponential think time; a query holds its nodes while
 it runs (a time proportional to its new tokens); the swapper ticks every 100 ms (section 5.3).
 
-Reported per variant (the paper's ablations: section 7.4 no dependencies, 7.5 LRU, 7.6 no LoRA reward):
+Reported per variant (the paper's ablations: section 6.6 no dependencies, 6.7 LRU, 6.8 no LoRA reward):
 KV hit ratio in blocks, LoRA cold starts, bytes swapped in on the critical path of a query (what Eq. 5
 calls the cold-start cost), bytes moved by the swapper, the share of HBM-resident KV blocks that cannot
-be matched because an ancestor is not resident ("invalid KV caches", sections 3.2 / 7.4), and the
-manager's own overheads against the paper's budget (section 7.8: < 0.5 ms per match and update, <= 5 ms
+be matched because an ancestor is not resident ("invalid KV caches", sections 2.3 / 6.6), and the
+manager's own overheads against the paper's budget (section 6.10: < 0.5 ms per match and update, <= 5 ms
 per swapping decision).
 """
 import heapq

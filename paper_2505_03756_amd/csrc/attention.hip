@@ -23,11 +23,14 @@ constexpr int BT = 16;   // token positions per block
 // One workgroup per (sequence, block, 256 vector-columns) unit.  A thread owns 16 bytes of a
 // token row (8 channels of one head, or 4 for fp32): it copies them into the K rows of the
 // unit's slots and, for V, gathers the unit's slots into registers and turns them into the
-// 16-slot runs of its channels.  A thread's runs are 256 contiguous bytes of the block and a
-// wave's are 16 KiB, so when the unit covers the whole block the runs pass through LDS once
-// and leave as 1 KiB-contiguous stores (full lines) instead of 16-byte pieces 256 bytes apart.
+// 16-slot runs of its channels.  A thread's runs are 256 contiguous bytes of the block and the
+// workgroup's 64 KiB, so the runs pass through LDS once and leave as 1 KiB-contiguous
+// non-temporal stores (whole lines) instead of 16-byte pieces 256 bytes apart.  A unit that
+// covers only part of its block (the first and the last block of a sequence's new tokens)
+// merges its slots into the runs already there: a partly filled block belongs to one sequence,
+// and this workgroup is the only writer of these columns of it.
 template <typename S, int D>
-__global__ __launch_bounds__(256) void kv_append_kernel(FlpAttnArgs a, const FlpAppendUnit* __restrict__ units) {
+__global__ __launch_bounds__(256, 2) void kv_append_kernel(FlpAttnArgs a, const FlpAppendUnit* __restrict__ units) {
   constexpr int EPV = 16 / (int)sizeof(S);          // elements per 16-byte vector
   constexpr int VPR = BT / EPV;                     // vectors per 16-slot V run
   constexpr int UPT = EPV * VPR;                    // 16-byte pieces of V a thread produces (16)
@@ -39,58 +42,79 @@ __global__ __launch_bounds__(256) void kv_append_kernel(FlpAttnArgs a, const Flp
   const int e0 = (blockIdx.y * 256 + tid) * EPV;
   const bool valid = e0 < row;
   const int ns = u.s1 - u.s0;
-  if (ns != BT && !valid) return;
+  const bool full = ns == BT;
   const int64_t blk = a.tables[(int64_t)u.seq * a.max_blocks + u.blk_idx];
   S* __restrict__ base = reinterpret_cast<S*>(a.pool) + blk * a.block_elems;
-  const S* __restrict__ kn = reinterpret_cast<const S*>(a.k_new) + (int64_t)u.t_first * row + e0;
-  const S* __restrict__ vn = reinterpret_cast<const S*>(a.v_new) + (int64_t)u.t_first * row + e0;
-  const int g = e0 / D, c0 = e0 - g * D;
-  S* __restrict__ kdst = base + ((int64_t)g * BT + u.s0) * D + c0;
-  if (ns == BT) {
-    if (valid) {
-      u32x4 vv[BT];
+  // V of the unit's 256 threads is 64 KiB contiguous in the block, thread t owning bytes 256 t ...
+  u32x4* __restrict__ vdst = reinterpret_cast<u32x4*>(base + (int64_t)a.n_kv * BT * D + (int64_t)blockIdx.y * 256 * EPV * BT);
+  if (valid) {
+    const S* __restrict__ kn = reinterpret_cast<const S*>(a.k_new) + (int64_t)u.t_first * row + e0;
+    const S* __restrict__ vn = reinterpret_cast<const S*>(a.v_new) + (int64_t)u.t_first * row + e0;
+    const int g = e0 / D, c0 = e0 - g * D;
+    S* __restrict__ kdst = base + ((int64_t)g * BT + u.s0) * D + c0;
+    u32x4 vv[BT];
+    if (full) {
 #pragma unroll
       for (int s = 0; s < BT; ++s) vv[s] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(vn + (int64_t)s * row));
 #pragma unroll
       for (int h = 0; h < 2; ++h) {                 // K in two halves to keep the register count down
         u32x4 kv[BT / 2];
 #pragma unroll
-        for (int s = 0; s < BT / 2; ++s) kv[s] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(kn + (int64_t)(h * (BT / 2) + s) * row));
+        for (int s = 0; s < BT / 2; ++s)
+          kv[s] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(kn + (int64_t)(h * (BT / 2) + s) * row));
 #pragma unroll
-        for (int s = 0; s < BT / 2; ++s) __builtin_nontemporal_store(kv[s], reinterpret_cast<u32x4*>(kdst + (h * (BT / 2) + s) * D));
+        for (int s = 0; s < BT / 2; ++s)
+          __builtin_nontemporal_store(kv[s], reinterpret_cast<u32x4*>(kdst + (h * (BT / 2) + s) * D));
       }
-      S vals[BT][EPV];
-      __builtin_memcpy(vals, vv, sizeof(vals));
+    } else {
+      // slot s of the block holds row s - s0 of the unit; slots outside the unit read row 0 and are masked out below
 #pragma unroll
-      for (int c = 0; c < EPV; ++c) {
-        S run[BT];
-#pragma unroll
-        for (int s = 0; s < BT; ++s) run[s] = vals[s][c];
-        u32x4 packed[VPR];
-        __builtin_memcpy(packed, run, sizeof(run));
-#pragma unroll
-        for (int v = 0; v < VPR; ++v) tr[tid * UPT + ((c * VPR + v) ^ (tid & 15))] = packed[v];
+      for (int s = 0; s < BT; ++s) {
+        const int r_ = (s >= u.s0 && s < u.s1) ? s - u.s0 : 0;
+        vv[s] = *reinterpret_cast<const u32x4*>(vn + (int64_t)r_ * row);
       }
+      for (int s = 0; s < ns; ++s)
+        *reinterpret_cast<u32x4*>(kdst + s * D) = *reinterpret_cast<const u32x4*>(kn + (int64_t)s * row);
     }
-    __syncthreads();
-    // V of the unit's 256 threads is 64 KiB contiguous in the block, thread t owning bytes 256 t ...:
-    // store j of a thread writes piece (256 j + tid), which thread (16 j + tid / 16) produced
-    u32x4* __restrict__ vdst = reinterpret_cast<u32x4*>(base + (int64_t)a.n_kv * BT * D + (int64_t)blockIdx.y * 256 * EPV * BT);
+    S vals[BT][EPV];
+    __builtin_memcpy(vals, vv, sizeof(vals));
 #pragma unroll
-    for (int j = 0; j < UPT; ++j) {
-      const int owner = 16 * j + (tid >> 4), piece = tid & 15;
-      if ((blockIdx.y * 256 + owner) * EPV < row) __builtin_nontemporal_store(tr[owner * UPT + (piece ^ (owner & 15))], vdst + 256 * j + tid);
-    }
-  } else {
-    S* __restrict__ vdst = base + (int64_t)a.n_kv * BT * D + ((int64_t)g * D + c0) * BT;
-    for (int s = 0; s < ns; ++s) {
-      *reinterpret_cast<u32x4*>(kdst + s * D) = *reinterpret_cast<const u32x4*>(kn + (int64_t)s * row);
-      S vals[EPV];
-      u32x4 raw = *reinterpret_cast<const u32x4*>(vn + (int64_t)s * row);
-      __builtin_memcpy(vals, &raw, 16);
+    for (int c = 0; c < EPV; ++c) {
+      S run[BT];
 #pragma unroll
-      for (int c = 0; c < EPV; ++c) vdst[c * BT + u.s0 + s] = vals[c];
+      for (int s = 0; s < BT; ++s) run[s] = vals[s][c];
+      u32x4 packed[VPR];
+      __builtin_memcpy(packed, run, sizeof(run));
+      if (!full) {
+        // the slots outside the unit keep what the block holds: word w of a run covers slots
+        // [w * SPW, (w + 1) * SPW), merged under a bit mask that is the same for every thread
+        constexpr int SPW = 4 / (int)sizeof(S);
+#pragma unroll
+        for (int v = 0; v < VPR; ++v) {
+          const u32x4 old = vdst[tid * UPT + c * VPR + v];
+#pragma unroll
+          for (int w = 0; w < 4; ++w) {
+            uint32_t mask = 0;
+#pragma unroll
+            for (int e = 0; e < SPW; ++e) {
+              const int sl = (4 * v + w) * SPW + e;
+              if (sl >= u.s0 && sl < u.s1) mask |= (SPW == 1 ? 0xffffffffu : 0xffffu << (16 * e));
+            }
+            packed[v][w] = (packed[v][w] & mask) | (old[w] & ~mask);
+          }
+        }
+      }
+#pragma unroll
+      for (int v = 0; v < VPR; ++v) tr[tid * UPT + ((c * VPR + v) ^ (tid & 15))] = packed[v];
     }
+  }
+  __syncthreads();
+  // store j of a thread writes piece (256 j + tid), which thread (16 j + tid / 16) produced
+#pragma unroll
+  for (int j = 0; j < UPT; ++j) {
+    const int owner = 16 * j + (tid >> 4), piece = tid & 15;
+    if ((blockIdx.y * 256 + owner) * EPV < row)
+      __builtin_nontemporal_store(tr[owner * UPT + (piece ^ (owner & 15))], vdst + 256 * j + tid);
   }
 }
 

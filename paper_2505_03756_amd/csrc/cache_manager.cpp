@@ -1,6 +1,6 @@
 // Host logic behind flcache.h: the usage-dependency tree of the cache manager (paper sections
 // 4.1-4.3) and the cost-model swapper (sections 5.1-5.3, Eq. 3-6), with the paper's ablation
-// switches (sections 7.4-7.6).  No device work: the block lists decided here are executed by
+// switches (sections 6.6-6.8).  No device work: the block lists decided here are executed by
 // flp_pool_swap_in / flp_pool_swap_out.
 //
 // Nodes live in a deque indexed by their id (ids are creation order and never reused, so ties in

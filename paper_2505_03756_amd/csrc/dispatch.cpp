@@ -293,10 +293,16 @@ extern "C" flp_status flp_lora_apply_paged(flp_pool* p, const flp_lora_batch* b,
   if (mfma_ok) {
     c.mt = b->n_tokens >= 2048 ? 2 : 1;
     const int tm = 16 * c.mt;
-    c.tiles_bound = (int32_t)((T + tm - 1) / tm) + (int32_t)std::min<size_t>((size_t)b->n_adapters, T);
+    // The number of segments is only known on the device.  The bounds (every adapter present, each adding a
+    // partly filled tile) size the buffers; the launches cover the tiles of up to 64 present adapters in one
+    // pass and loop for the rest, so that a pool of thousands of adapters does not launch thousands of
+    // workgroups that find nothing to do.
+    const int32_t seg_bound = (int32_t)std::min<size_t>((size_t)b->n_adapters, T);
+    c.tiles_bound = (int32_t)((T + tm - 1) / tm) + seg_bound;
+    c.tiles_grid = (std::min(c.tiles_bound, (int32_t)((T + tm - 1) / tm) + 64) + 7) / 8 * 8;
     // split K until about 2048 workgroups are in flight, in pieces of 128 coefficients
     int ks = 1;
-    while (ks < 8 && c.tiles_bound * ks < 2048 && b->d_in / (ks * 2) >= 256) ks *= 2;
+    while (ks < 8 && c.tiles_grid * ks < 2048 && b->d_in / (ks * 2) >= 256) ks *= 2;
     c.k_splits = ks;
     c.k_per_split = ((b->d_in + ks - 1) / ks + 127) / 128 * 128;
     c.v_rows = c.tiles_bound * tm;
@@ -305,7 +311,8 @@ extern "C" flp_status flp_lora_apply_paged(flp_pool* p, const flp_lora_batch* b,
     // (decode): narrow slabs, i.e. more waves, each gathering one piece
     c.cols_per_slab = c.mt == 2 ? 256 : 256 / nt;
     c.group_tokens = tm * (c.mt == 2 ? 8 : 1);
-    c.groups_bound = (int32_t)((T + c.group_tokens - 1) / c.group_tokens) + (int32_t)std::min<size_t>((size_t)b->n_adapters, T);
+    c.groups_bound = (int32_t)((T + c.group_tokens - 1) / c.group_tokens) + seg_bound;
+    c.groups_grid = (std::min(c.groups_bound, (int32_t)((T + c.group_tokens - 1) / c.group_tokens) + 64) + 7) / 8 * 8;
     const int rp = 16 * nt;
     v_elems = (size_t)ks * c.v_rows * b->n_proj * rp;
   }

@@ -146,9 +146,11 @@ struct FlpLoraMfma {
   int32_t k_splits, k_per_split;
   int32_t v_rows;              // rows of one split's partial v buffer (= tiles_bound * 16 * mt)
   int32_t cols_per_slab;
-  int32_t tiles_bound;         // host-side upper bound of the number of tiles
+  int32_t tiles_bound;         // host-side upper bound of the number of tiles (sizes the v buffer)
+  int32_t tiles_grid;          // tiles the shrink launch covers in one pass (multiple of 8); more are looped over
   int32_t group_tokens;        // tokens per tile group of the expand kernel (multiple of 16*mt)
   int32_t groups_bound;
+  int32_t groups_grid;         // tile groups the expand launch covers in one pass (multiple of 8)
   int32_t slabs;               // column slabs per projection (set by the launcher)
 };
 

@@ -78,20 +78,24 @@ __global__ __launch_bounds__(256) void lora_shrink_mfma_kernel(FlpLoraArgs a, Fl
   extern __shared__ float red[];                       // [4 waves][n_acc][64 lanes]
   // Each XCD (workgroups are placed on the 8 XCDs round-robin by their linear id) takes a contiguous
   // eighth of the tiles with all their k splits: tiles of one adapter are neighbours, so its A pages
-  // are fetched into one L2 instead of eight.
-  const int per_xcd = (c.tiles_bound + 7) / 8;
-  const int tile = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3) / c.k_splits, ks = (blockIdx.x >> 3) % c.k_splits;
+  // are fetched into one L2 instead of eight.  The launch covers gridDim.x / (8 k_splits) tiles per XCD
+  // in one pass; with more segments than the host allowed for, a workgroup takes several tiles in turn.
   const int n_seg = *a.n_seg;
-  if (tile >= a.tile_start[n_seg]) return;
+  const int n_tiles = a.tile_start[n_seg];
+  const int per_xcd = (n_tiles + 7) / 8;
+  const int ks = (blockIdx.x >> 3) % c.k_splits;
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, row = lane & 15, kg = lane >> 4;
+  const uint16_t* __restrict__ pool = reinterpret_cast<const uint16_t*>(a.pool);
+  const int rpb = (int)(a.block_elems / a.d_in);
+  for (int lt = (blockIdx.x >> 3) / c.k_splits; lt < per_xcd; lt += (gridDim.x >> 3) / c.k_splits) {
+  const int tile = (blockIdx.x & 7) * per_xcd + lt;
+  if (tile >= n_tiles) break;
   const int s = find_segment(a.tile_start, n_seg, tile);
   const int ad = a.seg_adapter[s];
   const int r = a.rank[ad] < 16 * NT ? a.rank[ad] : 16 * NT;
   const int TM = 16 * MT;
   const int pos0 = a.seg_start[s] + (tile - a.tile_start[s]) * TM;
   const int pos_end = a.seg_start[s + 1];
-  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, row = lane & 15, kg = lane >> 4;
-  const uint16_t* __restrict__ pool = reinterpret_cast<const uint16_t*>(a.pool);
-  const int rpb = (int)(a.block_elems / a.d_in);
 
   const uint16_t* xp[MT];
 #pragma unroll
@@ -169,6 +173,8 @@ __global__ __launch_bounds__(256) void lora_shrink_mfma_kernel(FlpLoraArgs a, Fl
     const int trow = 16 * mt + (ln >> 4) * 4 + i, rho = 16 * nt + (ln & 15);
     vout[((int64_t)trow * a.n_proj + p) * RP + rho] = sum;
   }
+  __syncthreads();                                     // the next tile reuses the reduction buffer
+  }
 }
 
 // ------------------------------------------------------------------------------- expand
@@ -186,17 +192,24 @@ __global__ __launch_bounds__(64) void lora_expand_mfma_kernel(FlpLoraArgs a, Flp
   // 8 XCDs round-robin by their linear id): they re-read the same rows of v and the same B pages,
   // which then stay in that XCD's L2.
   const int per_group = c.slabs * a.n_proj;
-  const int xcd = blockIdx.x & 7, q = blockIdx.x >> 3;
-  const int group = (q / per_group) * 8 + xcd, slab = (q % per_group) / a.n_proj, p = (q % per_group) % a.n_proj;
   const int n_seg = *a.n_seg;
-  if (group >= a.group_start[n_seg]) return;
+  const int n_groups = a.group_start[n_seg];
+  const int q_total = (n_groups + 7) / 8 * per_group;
+  const int xcd = blockIdx.x & 7;
+  const int lane = threadIdx.x, n = lane & 15, kg = lane >> 4, kq = kg & 1, lo_half = kg >> 1, m = lane & 15;
+  const uint16_t* __restrict__ pool = reinterpret_cast<const uint16_t*>(a.pool);
+  // the launch covers gridDim.x / 8 (group, slab, projection) items per XCD in one pass; with more segments
+  // than the host allowed for, a wave takes several items in turn
+  for (int q = blockIdx.x >> 3; q < q_total; q += gridDim.x >> 3) {
+  const int group = (q / per_group) * 8 + xcd, slab = (q % per_group) / a.n_proj, p = (q % per_group) % a.n_proj;
+  if (group >= n_groups) continue;
   const flp_lora_proj& pr = a.proj[p];
   const int slab_begin = slab * c.cols_per_slab;
-  if (slab_begin >= pr.d_out) return;
+  if (slab_begin >= pr.d_out) continue;
   const int s = find_segment(a.group_start, n_seg, group);
   const int ad = a.seg_adapter[s];
   const int r = a.rank[ad] < 16 * NT ? a.rank[ad] : 16 * NT;
-  if (r <= 0) return;
+  if (r <= 0) continue;
   const float sc = a.scale[ad];
   const int RP = 16 * NT, TM = 16 * c.mt;
   const int off0 = (group - a.group_start[s]) * c.group_tokens;       // first token of the group inside its segment
@@ -204,8 +217,6 @@ __global__ __launch_bounds__(64) void lora_expand_mfma_kernel(FlpLoraArgs a, Flp
   const int pos_end = a.seg_start[s + 1];
   const int pos_stop = pos0 + c.group_tokens < pos_end ? pos0 + c.group_tokens : pos_end;
   const int64_t vrow0 = (int64_t)a.tile_start[s] * TM + off0;         // the segment's rows of v are contiguous
-  const int lane = threadIdx.x, n = lane & 15, kg = lane >> 4, kq = kg & 1, lo_half = kg >> 1, m = lane & 15;
-  const uint16_t* __restrict__ pool = reinterpret_cast<const uint16_t*>(a.pool);
   const int rpb = (int)(a.block_elems / pr.d_out);
 
   // page rows of B for this lane's 8 ranks of every rank tile
@@ -331,6 +342,7 @@ __global__ __launch_bounds__(64) void lora_expand_mfma_kernel(FlpLoraArgs a, Flp
       tok = tok_next;
     }
   }
+  }
 }
 
 template <typename L, int MT, int NT>
@@ -342,14 +354,14 @@ flp_status launch_pair(const FlpLoraArgs& a, const FlpLoraMfma& c, hipStream_t s
                                     hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));
     attr_set = true;
   }
-  hipLaunchKernelGGL((lora_shrink_mfma_kernel<L, MT, NT>), dim3((unsigned)((c.tiles_bound + 7) / 8 * 8 * c.k_splits)),
+  hipLaunchKernelGGL((lora_shrink_mfma_kernel<L, MT, NT>), dim3((unsigned)(c.tiles_grid * c.k_splits)),
                      dim3(256), smem, stream, a, c);
   FLP_TRY_HIP(hipGetLastError());
   int max_dout = 0;
   for (int p = 0; p < a.n_proj; ++p) max_dout = a.proj[p].d_out > max_dout ? a.proj[p].d_out : max_dout;
   FlpLoraMfma ce = c;
   ce.slabs = (max_dout + c.cols_per_slab - 1) / c.cols_per_slab;
-  const int64_t n_wg = (int64_t)((c.groups_bound + 7) / 8) * 8 * ce.slabs * a.n_proj;
+  const int64_t n_wg = (int64_t)c.groups_grid * ce.slabs * a.n_proj;
   if (n_wg > INT32_MAX) {
     flp_set_error("LoRA (matrix-core path): %lld workgroups, too many for one launch", (long long)n_wg);
     return FLP_ENOTSUP;

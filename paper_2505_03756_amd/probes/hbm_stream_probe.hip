@@ -130,6 +130,45 @@ __global__ __launch_bounds__(256) void rmw_kernel(u32x4* __restrict__ buf, size_
   for (; i < n; i += stride) buf[i] = buf[i] + 1u;
 }
 
+// Update in place of a [rows][4096] matrix of 16-bit elements (8 KiB rows) by one-wave workgroups in the
+// lane layout of the LoRA expand kernel: 16 rows x 256 columns per step, a lane holding 16 consecutive
+// columns of one row (two 16-byte accesses), the four lanes of a row covering a 128-byte line, four such
+// 64-column chunks per step.  MODE 0: a wave keeps its 256-column slab and walks down 256 rows in 16 steps
+// (what the expand kernel does: the B fragments of the slab stay in registers).  MODE 1: a wave keeps its
+// 16 rows and walks along them through the 16 slabs (each row is touched as one contiguous 8 KiB run).
+template <int MODE, bool NT>
+__global__ __launch_bounds__(64) void rmw_tile_kernel(uint16_t* __restrict__ y, int n_rows) {
+  const int lane = threadIdx.x, n = lane & 15, kg = lane >> 4;
+  for (int step = 0; step < 16; ++step) {
+    int row, slab;
+    if (MODE == 0) {
+      row = (blockIdx.x >> 4) * 256 + step * 16 + n;
+      slab = blockIdx.x & 15;
+    } else {
+      row = blockIdx.x * 16 + n;
+      slab = step;
+    }
+    if (row >= n_rows) return;
+    u32x4* p = reinterpret_cast<u32x4*>(y + (size_t)row * 4096 + 256 * slab + 16 * kg);
+    u32x4 r[4][2];
+#pragma unroll
+    for (int ch = 0; ch < 4; ++ch) {
+      r[ch][0] = NT ? __builtin_nontemporal_load(p + 8 * ch) : p[8 * ch];
+      r[ch][1] = NT ? __builtin_nontemporal_load(p + 8 * ch + 1) : p[8 * ch + 1];
+    }
+#pragma unroll
+    for (int ch = 0; ch < 4; ++ch) {
+      if (NT) {
+        __builtin_nontemporal_store(r[ch][0] + 1u, p + 8 * ch);
+        __builtin_nontemporal_store(r[ch][1] + 1u, p + 8 * ch + 1);
+      } else {
+        p[8 * ch] = r[ch][0] + 1u;
+        p[8 * ch + 1] = r[ch][1] + 1u;
+      }
+    }
+  }
+}
+
 template <typename F>
 float best_ms(F launch) {
   hipEvent_t e0, e1;
@@ -185,6 +224,21 @@ int main() {
     t = best_ms([&] { hipLaunchKernelGGL(rmw_kernel<8>, dim3(g), dim3(256), 0, 0, a, n); });
     std::printf("%-28s %8d %10.3f %12.2f\n", "update in place, 8 x 16 B", g, t, 2.0 * bytes / t / 1e9);
     std::fflush(stdout);
+  }
+  // the LoRA expand pattern: 3 x 18944 rows of 8 KiB (what the q,k,v call of the 7b_prefill batch updates)
+  {
+    const int n_rows = 3 * 18944;
+    const double moved = 2.0 * n_rows * 8192.0;
+    uint16_t* y = reinterpret_cast<uint16_t*>(a);
+    const int g0 = n_rows / 256 * 16, g1 = n_rows / 16;
+    float t = best_ms([&] { hipLaunchKernelGGL((rmw_tile_kernel<0, false>), dim3(g0), dim3(64), 0, 0, y, n_rows); });
+    std::printf("%-44s %8d %10.3f %12.2f\n", "tile update, wave keeps its 256 columns", g0, t, moved / t / 1e9);
+    t = best_ms([&] { hipLaunchKernelGGL((rmw_tile_kernel<0, true>), dim3(g0), dim3(64), 0, 0, y, n_rows); });
+    std::printf("%-44s %8d %10.3f %12.2f\n", "  same, non-temporal", g0, t, moved / t / 1e9);
+    t = best_ms([&] { hipLaunchKernelGGL((rmw_tile_kernel<1, false>), dim3(g1), dim3(64), 0, 0, y, n_rows); });
+    std::printf("%-44s %8d %10.3f %12.2f\n", "tile update, wave keeps its 16 rows", g1, t, moved / t / 1e9);
+    t = best_ms([&] { hipLaunchKernelGGL((rmw_tile_kernel<1, true>), dim3(g1), dim3(64), 0, 0, y, n_rows); });
+    std::printf("%-44s %8d %10.3f %12.2f\n", "  same, non-temporal", g1, t, moved / t / 1e9);
   }
   CHECK(hipFree(a));
   CHECK(hipFree(b));

@@ -85,7 +85,7 @@ class LayerConfig:
     new_range: Tuple[int, int]      # inclusive (used by prefill sequences)
     decode_frac: float = 0.0        # fraction of sequences with exactly 1 new token
     lora_scale: float = 1.0
-    adapter_dist: str = "uniform"   # "uniform" | "zipf"
+    adapter_dist: str = "uniform"   # "uniform" | "zipf" | "distinct" | "skewed" (see _seq_adapters)
     zipf_alpha: float = 1.0
     swap_in_frac: float = 0.0       # share of reusable blocks that start on the host tier
     swap_out_frac: float = 0.0      # share (of reusable count) of idle blocks swapped out first
@@ -93,6 +93,7 @@ class LayerConfig:
     mlp_dim: int = 0
     lora_std: float = 0.02
     seed: int = 20250503
+    skew_std: float = 32.0          # standard deviation, in adapter ids, of the "skewed" distribution
 
     @property
     def block_elems(self) -> int:
@@ -211,6 +212,22 @@ def _popularity(cfg: LayerConfig, rng) -> np.ndarray:
     return p
 
 
+def _seq_adapters(cfg: LayerConfig, rng, S: int) -> np.ndarray:
+    """One adapter id per sequence.  "uniform" and "zipf" draw from a popularity vector; the other two
+    are the paper's remaining LoRA distributions (section 6.9, the 1000 / 2000 LoRA experiment):
+    "distinct" hands the adapters out in turn (sequence i gets adapter (first + i) mod n, first seeded),
+    "skewed" rounds a normal deviate around the middle id with standard deviation skew_std."""
+    n = cfg.n_adapters
+    if cfg.adapter_dist == "distinct":
+        first = int(rng.integers(0, n))
+        return ((first + np.arange(S)) % n).astype(np.int32)
+    if cfg.adapter_dist == "skewed":
+        ids = np.rint(rng.normal(n / 2.0, cfg.skew_std, size=S)).astype(np.int64)
+        return np.clip(ids, 0, n - 1).astype(np.int32)
+    pop = _popularity(cfg, rng)
+    return rng.choice(n, size=S, p=pop).astype(np.int32)
+
+
 def make_step(cfg: LayerConfig, seed: Optional[int] = None,
               alloc_dev: Optional[Callable[[int], np.ndarray]] = None,
               alloc_host: Optional[Callable[[int], np.ndarray]] = None,
@@ -260,8 +277,7 @@ def make_step(cfg: LayerConfig, seed: Optional[int] = None,
     cu_new = np.zeros(S + 1, dtype=np.int32)
     cu_new[1:] = np.cumsum(new_len)
     T = int(cu_new[-1])
-    pop = _popularity(cfg, rng)
-    seq_adapter = rng.choice(cfg.n_adapters, size=S, p=pop).astype(np.int32)
+    seq_adapter = _seq_adapters(cfg, rng, S)
     token_adapter = np.repeat(seq_adapter, new_len).astype(np.int32)
 
     # ---- adapters present in the batch get pages --------------------------

@@ -168,7 +168,7 @@ def test_errors_leave_the_cache_unchanged():
 
 
 def test_overheads_stay_within_the_papers_budget():
-    """Section 7.8 of the paper: matching and updating below 0.5 ms, the swapping decision within 5 ms.
+    """Section 6.10 of the paper: matching and updating below 0.5 ms, the swapping decision within 5 ms.
     Tree of 100 LoRAs and 60 000 KV blocks (a 15 GiB pool of 256 KiB blocks), queries of 1024 tokens."""
     bt = 16
     n_dev, n_host = 60000, 60000

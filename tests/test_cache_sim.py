@@ -13,7 +13,7 @@ def test_short_trace(variant):
     assert r["hbm_usage_mean"] <= 0.97
     if variant != "no_dependencies":
         assert r["invalid_kv_share_mean"] == 0.0          # section 4.2: every resident KV cache is a valid one
-    assert r["match_update_us_mean"] < 500.0              # the paper's budget (section 7.8)
+    assert r["match_update_us_mean"] < 500.0              # the paper's budget (section 6.10)
     assert r["tick_ms_mean"] < 5.0
 
 

@@ -137,6 +137,21 @@ LORA_CASES = {
                                                 n_adapters=60, ranks=(8, 16, 32, 64), n_dev_blocks=2500,
                                                 swap_in_frac=0.0, seed=83),
     # rank 64 with 32-token tiles and a k/v width different from q/o (grouped-query shapes)
+    # the paper's LoRA distributions at 1000-2000 LoRAs (section 6.9): adapters handed out in turn (every
+    # sequence its own adapter, hundreds of short segments in one tiled launch), ...
+    "f16_distinct_2000": lambda: small_cfg("f16", hidden=1024, n_q_heads=8, n_kv_heads=8, n_seqs=300,
+                                           prefix_range=(0, 0), new_range=(2, 40), n_adapters=2000, ranks=(16,),
+                                           adapter_dist="distinct", n_dev_blocks=4000, swap_in_frac=0.0, seed=85),
+    # ... uniform over 2000 (almost all distinct), mixed ranks ...
+    "bf16_uniform_2000": lambda: small_cfg("bf16", hidden=1024, n_q_heads=8, n_kv_heads=8, n_seqs=260,
+                                           prefix_range=(0, 0), new_range=(1, 24), n_adapters=2000,
+                                           ranks=(8, 16, 32, 64), adapter_dist="uniform", n_dev_blocks=6000,
+                                           swap_in_frac=0.0, seed=86),
+    # ... and a Gaussian over the ids (a few dozen adapters carry the batch), as a decode batch
+    "bf16_skewed_1000_decode": lambda: small_cfg("bf16", hidden=1024, n_q_heads=8, n_kv_heads=8, n_seqs=700,
+                                                 prefix_range=(0, 0), new_range=(1, 1), decode_frac=1.0,
+                                                 n_adapters=1000, ranks=(16, 32), adapter_dist="skewed", skew_std=12.0,
+                                                 n_dev_blocks=6000, swap_in_frac=0.0, seed=87),
     "f16_rank64_gqa": lambda: small_cfg("f16", hidden=1024, n_q_heads=8, n_kv_heads=2, n_seqs=30,
                                         prefix_range=(0, 0), new_range=(30, 120), n_adapters=5, ranks=(64,),
                                         n_dev_blocks=1500, swap_in_frac=0.0, seed=84),
