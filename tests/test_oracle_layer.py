@@ -1,0 +1,196 @@
+"""Pins of the layer-glue oracle (oracle/layer_oracle.py) against what mathematics fixes: closed forms,
+invariants, group properties of the rotation, a library routine where a step reduces to one."""
+import math
+
+import numpy as np
+import pytest
+
+import oracle
+from oracle import layer_oracle as lo
+from paper_2505_03756_amd import workload as wl
+
+RNG = np.random.default_rng(20250610)
+
+
+# ------------------------------------------------------------------------------- element types
+@pytest.mark.parametrize("dtype", ["f32", "f16", "bf16"])
+def test_round_store_matches_scalar_oracle_and_generator(dtype):
+    v = np.concatenate([RNG.normal(0, 1, 4000), RNG.normal(0, 1e-6, 500), RNG.normal(0, 3e4, 500),
+                        [0.0, -0.0, 1.0, 65504.0, 1 + 2.0 ** -8, 1 + 3 * 2.0 ** -8, 1 + 2.0 ** -11, 6e-8, 1e-40]])
+    st, val = lo.round_store(v, dtype)
+    assert np.array_equal(val, oracle.round_to_dtype(v, dtype))           # the C oracle's scalar routine
+    assert np.array_equal(lo.load(st, dtype), val)                         # bits <-> values
+    if dtype == "f16":
+        with np.errstate(over="ignore"):
+            assert np.array_equal(st, v.astype(np.float16).view(np.uint16))
+
+
+def test_bf16_ties_go_to_even():
+    # 1 + 2^-8 lies halfway between 1 and 1 + 2^-7: even mantissa wins; 1 + 3*2^-8 goes up to 1 + 2^-6
+    _, val = lo.round_store(np.array([1 + 2.0 ** -8, 1 + 3 * 2.0 ** -8, 1 + 2.0 ** -8 + 2.0 ** -20]), "bf16")
+    assert val.tolist() == [1.0, 1 + 2.0 ** -6, 1 + 2.0 ** -7]
+
+
+# ------------------------------------------------------------------------------- rmsnorm
+def test_rmsnorm_closed_form_3_4():
+    y = lo.rmsnorm(np.array([[3.0, 4.0]]), np.array([1.0, 1.0]), eps=0.0)
+    assert np.allclose(y, np.array([[3.0, 4.0]]) / math.sqrt(12.5), rtol=0, atol=1e-15)
+
+
+def test_rmsnorm_invariants():
+    x = RNG.normal(0, 2.0, (5, 64))
+    w = RNG.normal(1, 0.1, 64)
+    y1 = lo.rmsnorm(x, np.ones(64), eps=0.0)
+    assert np.allclose(np.sqrt(np.mean(y1 * y1, axis=1)), 1.0, atol=1e-14)          # unit root mean square
+    assert np.allclose(lo.rmsnorm(7.5 * x, w, eps=0.0), lo.rmsnorm(x, w, eps=0.0), atol=1e-13)   # scale free
+    assert np.allclose(lo.rmsnorm(x, w, eps=0.0), y1 * w, atol=1e-14)               # weight is a plain factor
+    c = lo.rmsnorm(np.full((1, 16), -3.0), np.arange(16.0), eps=0.0)
+    assert np.allclose(c, -np.arange(16.0), atol=1e-14)                             # constant row -> sign * w
+    # eps enters under the root next to the mean square
+    assert np.allclose(lo.rmsnorm(np.array([[2.0, 2.0]]), np.ones(2), eps=5.0), 2.0 / 3.0, atol=1e-15)
+
+
+# ------------------------------------------------------------------------------- rope
+def test_rope_d2_is_a_plane_rotation():
+    x = np.array([[[1.0, 0.0]], [[0.0, 1.0]], [[2.0, -1.0]]])
+    pos = np.array([0.5, 0.5, 3.0])
+    y = lo.rope(x, pos, theta=10000.0)                    # d = 2: one pair, frequency theta^0 = 1
+    for t in range(3):
+        c, s = math.cos(pos[t]), math.sin(pos[t])
+        R = np.array([[c, -s], [s, c]])
+        assert np.allclose(y[t, 0], R @ x[t, 0], atol=1e-15)
+
+
+def test_rope_frequencies_and_pairing():
+    # d = 4, theta = 10000: pair 0 = channels (0, 2) at frequency 1, pair 1 = channels (1, 3) at 10000^(-1/2) = 0.01
+    x = np.zeros((1, 1, 4))
+    x[0, 0, 1] = 1.0
+    y = lo.rope(x, np.array([25.0]), theta=10000.0)
+    assert np.allclose(y[0, 0], [0.0, math.cos(0.25), 0.0, math.sin(0.25)], atol=1e-15)
+    x = np.zeros((1, 1, 4))
+    x[0, 0, 0] = 1.0
+    y = lo.rope(x, np.array([2.0]), theta=10000.0)
+    assert np.allclose(y[0, 0], [math.cos(2.0), 0.0, math.sin(2.0), 0.0], atol=1e-15)
+
+
+def test_rope_group_properties():
+    x = RNG.normal(0, 1, (6, 3, 16))
+    k = RNG.normal(0, 1, (6, 3, 16))
+    p = np.array([0, 1, 5, 17, 100, 4000], dtype=np.float64)
+    assert np.allclose(lo.rope(x, np.zeros(6)), x, atol=0)                                   # position 0: identity
+    assert np.allclose(lo.rope(lo.rope(x, p), 3 * p + 2), lo.rope(x, 4 * p + 2), atol=1e-11)  # angles add
+    y = lo.rope(x, p)
+    half = 8
+    assert np.allclose(y[..., :half] ** 2 + y[..., half:] ** 2, x[..., :half] ** 2 + x[..., half:] ** 2, atol=1e-12)
+    # scores depend on the distance only: <rope(q, m), rope(k, n)> = <rope(q, m + s), rope(k, n + s)>
+    a = np.einsum("thd,thd->th", lo.rope(x, p), lo.rope(k, p[::-1].copy()))
+    b = np.einsum("thd,thd->th", lo.rope(x, p + 37), lo.rope(k, p[::-1] + 37))
+    assert np.allclose(a, b, atol=1e-10)
+
+
+# ------------------------------------------------------------------------------- silu
+def test_silu_mul_values_and_identities():
+    g = np.array([0.0, 1.0, -1.0, 30.0, -30.0])
+    y = lo.silu_mul(g, np.ones(5))
+    assert y[0] == 0.0
+    assert abs(y[1] - 0.7310585786300049) < 1e-15           # 1 / (1 + e^-1)
+    assert abs(y[3] - 30.0) < 1e-11 and abs(y[4]) < 1e-11   # x for large x, 0 for very negative x
+    x = RNG.normal(0, 3, 1000)
+    assert np.allclose(lo.silu_mul(x, np.ones(1000)) - lo.silu_mul(-x, np.ones(1000)), x, atol=1e-14)   # silu(x) - silu(-x) = x
+    u = RNG.normal(0, 1, 1000)
+    assert np.allclose(lo.silu_mul(x, u), lo.silu_mul(x, np.ones(1000)) * u, atol=1e-15)                  # up is a plain factor
+    # the minimum of x * sigmoid(x) is about -0.27846 near x = -1.27846
+    xs = np.linspace(-3, 0, 300001)
+    ys = lo.silu_mul(xs, np.ones_like(xs))
+    assert abs(ys.min() + 0.2784645) < 1e-6 and abs(xs[ys.argmin()] + 1.2784645) < 1e-4
+
+
+# ------------------------------------------------------------------------------- the composed layer
+def small_cfg(dtype="f32", **kw):
+    base = dict(name="layer_small", dtype=dtype, hidden=64, n_q_heads=2, n_kv_heads=2, head_dim=64, n_dev_blocks=96,
+                n_host_blocks=8, n_adapters=3, ranks=(4,), projections=("q", "k", "v", "o", "gate", "up", "down"),
+                n_seqs=3, prefix_range=(0, 20), new_range=(1, 6), mlp_dim=128, seed=31)
+    base.update(kw)
+    return wl.LayerConfig(**base)
+
+
+def make_weights(cfg, rng, zero=()):
+    W = {"in_norm": rng.normal(1, 0.1, cfg.hidden), "post_norm": rng.normal(1, 0.1, cfg.hidden)}
+    for n in ("q", "k", "v", "o", "gate", "up", "down"):
+        d_in, d_out = cfg.proj_dims(n)
+        W[n] = np.zeros((d_out, d_in)) if n in zero else rng.normal(0, 1 / math.sqrt(d_in), (d_out, d_in))
+    return {k: lo.round_store(v, cfg.dtype)[0] for k, v in W.items()}
+
+
+def pool_image(step):
+    cfg = step.cfg
+    pool = np.zeros((cfg.n_dev_blocks, cfg.block_elems), dtype=wl.storage_dtype(cfg.dtype))
+    pool[step.content_ids] = step.content
+    return pool
+
+
+def positions_of(step):
+    return np.concatenate([step.prefix_len[i] + np.arange(step.cu_new[i + 1] - step.cu_new[i])
+                           for i in range(len(step.prefix_len))]).astype(np.int32)
+
+
+def test_layer_with_silent_branches_is_the_identity():
+    # W_o = 0 and W_down = 0, all LoRA B rows zero -> both residual branches add exactly nothing
+    cfg = small_cfg()
+    step = wl.make_step(cfg)
+    pool = pool_image(step)
+    for n in ("o", "down"):                      # zero the B rows of these projections in the pool
+        pr = step.proj[n]
+        for a in np.flatnonzero(step.rank > 0):
+            for rho in range(int(step.rank[a])):
+                oracle.lora_write_row(pool, cfg.dtype, step.lora_tables[pr.b_tab_off[a]:], int(pr.b_row_base[a]) + rho,
+                                      np.zeros(pr.d_out))
+    W = make_weights(cfg, np.random.default_rng(1), zero=("o", "down"))
+    h0, _ = lo.round_store(np.random.default_rng(2).normal(0, 1, (step.n_tokens, cfg.hidden)), cfg.dtype)
+    h2, _ = lo.layer_forward(cfg, step, pool, W, h0, positions_of(step))
+    assert np.array_equal(h2, h0)
+
+
+def test_layer_single_token_reduces_to_matrix_products():
+    # one sequence, no prefix, one new token: attention returns v itself, rope at position 0 is the identity;
+    # with no adapter on the token every projection is a plain matrix product (library matmul)
+    cfg = small_cfg(n_seqs=1, prefix_range=(0, 0), new_range=(1, 1))
+    step = wl.make_step(cfg)
+    step.token_adapter[:] = -1
+    pool = pool_image(step)
+    W = make_weights(cfg, np.random.default_rng(3))
+    Wv = {k: lo.load(v, cfg.dtype) for k, v in W.items()}
+    h0, h0v = lo.round_store(np.random.default_rng(4).normal(0, 1, (1, cfg.hidden)), cfg.dtype)
+    h2, inter = lo.layer_forward(cfg, step, pool, W, h0, np.zeros(1, np.int32))
+    f32 = lambda a: a.astype(np.float32).astype(np.float64)            # cfg is f32: one rounding per tensor
+    n1 = f32(h0v / np.sqrt(np.mean(h0v ** 2) + 1e-5) * Wv["in_norm"])
+    v = f32(n1 @ Wv["v"].T)
+    o = f32(v @ Wv["o"].T)                                             # softmax over one key = 1
+    h1 = f32(h0v + o)
+    n2 = f32(h1 / np.sqrt(np.mean(h1 ** 2) + 1e-5) * Wv["post_norm"])
+    g, u = f32(n2 @ Wv["gate"].T), f32(n2 @ Wv["up"].T)
+    act = f32(g / (1 + np.exp(-g)) * u)
+    want = f32(h1 + f32(act @ Wv["down"].T))
+    assert np.allclose(lo.load(h2, cfg.dtype), want, rtol=0, atol=2e-6)
+    assert np.allclose(lo.load(inter["attn"], cfg.dtype), v, rtol=0, atol=1e-6)
+
+
+def test_layer_lora_branch_enters_every_projection():
+    # doubling every adapter's scale changes each projection's output by exactly its LoRA branch
+    cfg = small_cfg()
+    step = wl.make_step(cfg)
+    W = make_weights(cfg, np.random.default_rng(5))
+    h0, _ = lo.round_store(np.random.default_rng(6).normal(0, 1, (step.n_tokens, cfg.hidden)), cfg.dtype)
+    pos = positions_of(step)
+    _, a = lo.layer_forward(cfg, step, pool_image(step), W, h0, pos)
+    step.scale[:] = 0.0
+    _, b = lo.layer_forward(cfg, step, pool_image(step), W, h0, pos)
+    has = step.token_adapter >= 0
+    assert has.any()
+    for n in ("q", "v", "o", "gate", "down"):
+        key = {"q": "q", "v": "v", "o": "o", "gate": "gate", "down": "down"}[n]
+        da = np.abs(lo.load(a[key], cfg.dtype) - lo.load(b[key], cfg.dtype))
+        assert da[has].max() > 1e-4, n                  # the branch is there ...
+    n1 = lo.load(b["n1"], cfg.dtype)
+    Wq = lo.load(W["v"], cfg.dtype)
+    assert np.allclose(lo.load(b["v"], cfg.dtype), (n1 @ Wq.T).astype(np.float32), atol=1e-6)   # ... and scale 0 leaves the base
