@@ -164,11 +164,12 @@ flp_status flp_paged_prefix_attention(flp_pool* pool, const flp_attn_batch* batc
 
 typedef struct {
   int32_t d_out;
-  int32_t reserved;
+  int32_t w_base_layout;          /* 0: w_base is [d_in, d_out]; 1: w_base is [d_out, d_in] (one row per
+                                     output feature, a linear layer's weight: no transposition pass)  */
   int64_t ld_y;                   /* elements between rows of y (>= d_out)                    */
   void*          y;               /* device [T, ld_y], pool dtype, in/out                     */
-  const void*    w_base;          /* device [d_in, d_out] row-major, pool dtype, or NULL (y already
-                                     holds the base); 16-bit pools need d_in % 64 == 0           */
+  const void*    w_base;          /* device, row-major in the layout above, pool dtype, or NULL (y
+                                     already holds the base); 16-bit pools need d_in % 64 == 0   */
   const int32_t* a_tab_off;       /* device int32[n_adapters]                                 */
   const int32_t* a_row_base;      /* device int32[n_adapters]                                 */
   const int32_t* b_tab_off;       /* device int32[n_adapters]                                 */

@@ -262,6 +262,10 @@ extern "C" flp_status flp_lora_apply_paged(flp_pool* p, const flp_lora_batch* b,
   }
   for (int q = 0; q < b->n_proj; ++q) {
     const flp_lora_proj& pr = b->proj[q];
+    if (pr.w_base_layout != 0 && pr.w_base_layout != 1) {
+      flp_set_error("flp_lora_apply_paged: projection %d: w_base_layout %d is neither 0 nor 1", q, pr.w_base_layout);
+      return FLP_EINVAL;
+    }
     if (pr.d_out <= 0 || pr.ld_y < pr.d_out || pr.d_out % epl || pr.ld_y % epl || pr.d_out > p->block_elems || !pr.y ||
         !aligned16(pr.y) || !pr.a_tab_off || !pr.a_row_base || !pr.b_tab_off || !pr.b_row_base) {
       flp_set_error("flp_lora_apply_paged: projection %d has bad sizes or null/misaligned pointers", q);
@@ -319,7 +323,8 @@ extern "C" flp_status flp_lora_apply_paged(flp_pool* p, const flp_lora_batch* b,
   size_t wt_bytes = 0;                         // transposed copy of the widest dense base matrix
   if (p->elem_bytes == 2)
     for (int q = 0; q < b->n_proj; ++q)
-      if (b->proj[q].w_base) wt_bytes = std::max(wt_bytes, (size_t)b->d_in * b->proj[q].d_out * 2);
+      if (b->proj[q].w_base && b->proj[q].w_base_layout == 0)
+        wt_bytes = std::max(wt_bytes, (size_t)b->d_in * b->proj[q].d_out * 2);
   wt_bytes = (wt_bytes + 255) & ~(size_t)255;
   size_t base_bytes[FLP_MAX_PROJ] = {0, 0, 0, 0}, base_total = 0;   // unrounded base terms (16-bit pools)
   if (p->elem_bytes == 2)
@@ -365,8 +370,9 @@ extern "C" flp_status flp_lora_apply_paged(flp_pool* p, const flp_lora_batch* b,
     for (int q = 0; q < b->n_proj; ++q) {
       if (!b->proj[q].w_base) continue;
       float* y32 = p->elem_bytes == 2 ? (float*)basep : nullptr;
-      FLP_TRY(flp_launch_base_gemm(p->cfg.dtype, b->x, b->ld_x, b->proj[q].w_base, b->proj[q].y, b->proj[q].ld_y,
-                                   b->n_tokens, b->proj[q].d_out, b->d_in, wt, y32, stream));
+      FLP_TRY(flp_launch_base_gemm(p->cfg.dtype, b->x, b->ld_x, b->proj[q].w_base, b->proj[q].w_base_layout,
+                                   b->proj[q].y, b->proj[q].ld_y, b->n_tokens, b->proj[q].d_out, b->d_in, wt, y32,
+                                   stream));
       a.base32[q] = y32;
       basep += base_bytes[q];
     }

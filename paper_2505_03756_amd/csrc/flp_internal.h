@@ -159,5 +159,5 @@ flp_status flp_launch_lora_segment(int32_t T, const int32_t* token_adapter, int3
                                    int32_t* tile_start, int32_t tg, int32_t* group_start, hipStream_t stream);
 flp_status flp_launch_lora_mfma(int dtype, const FlpLoraArgs& a, const FlpLoraMfma& c, hipStream_t stream);
 flp_status flp_launch_lora_simple(int dtype, const FlpLoraArgs& a, hipStream_t stream);
-flp_status flp_launch_base_gemm(int dtype, const void* x, int64_t ld_x, const void* w, void* y, int64_t ld_y, int M,
-                                int N, int K, void* wt_scratch, float* y32, hipStream_t stream);
+flp_status flp_launch_base_gemm(int dtype, const void* x, int64_t ld_x, const void* w, int w_layout, void* y,
+                                int64_t ld_y, int M, int N, int K, void* wt_scratch, float* y32, hipStream_t stream);

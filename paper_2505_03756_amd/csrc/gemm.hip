@@ -163,25 +163,28 @@ __global__ __launch_bounds__(256, 2) void gemm_nt_kernel(const uint16_t* __restr
 }
 
 __global__ __launch_bounds__(256) void gemm_f32_kernel(const float* __restrict__ x, int64_t ld_x,
-                                                       const float* __restrict__ w, float* __restrict__ y,
-                                                       int64_t ld_y, int M, int N, int K) {
+                                                       const float* __restrict__ w, int64_t w_k_stride,
+                                                       int64_t w_n_stride, float* __restrict__ y, int64_t ld_y, int M,
+                                                       int N, int K) {
   const int n = blockIdx.x * 256 + threadIdx.x, m = blockIdx.y;
   if (n >= N) return;
   float acc = 0.f;
-  for (int k = 0; k < K; ++k) acc = fmaf(x[(int64_t)m * ld_x + k], w[(int64_t)k * N + n], acc);
+  for (int k = 0; k < K; ++k) acc = fmaf(x[(int64_t)m * ld_x + k], w[k * w_k_stride + n * w_n_stride], acc);
   y[(int64_t)m * ld_y + n] = acc;
 }
 
 }  // namespace
 
-// y[M, N] = x[M, K] . w[K, N].  `wt_scratch` (16-bit types only) must hold N*K elements; `y32`
-// (16-bit types, optional) receives the unrounded product as dense fp32 [M, N].
-flp_status flp_launch_base_gemm(int dtype, const void* x, int64_t ld_x, const void* w, void* y, int64_t ld_y, int M,
-                                int N, int K, void* wt_scratch, float* y32, hipStream_t stream) {
+// y[M, N] = x[M, K] . W with w stored [K, N] (w_layout 0) or [N, K] (w_layout 1).  `wt_scratch` (16-bit
+// types with layout 0 only) must hold N*K elements; `y32` (16-bit types, optional) receives the
+// unrounded product as dense fp32 [M, N].
+flp_status flp_launch_base_gemm(int dtype, const void* x, int64_t ld_x, const void* w, int w_layout, void* y,
+                                int64_t ld_y, int M, int N, int K, void* wt_scratch, float* y32, hipStream_t stream) {
   if (M <= 0 || N <= 0 || K <= 0) return FLP_OK;
   if (dtype == FLP_F32) {
     hipLaunchKernelGGL(gemm_f32_kernel, dim3((N + 255) / 256, M), dim3(256), 0, stream, (const float*)x, ld_x,
-                       (const float*)w, (float*)y, ld_y, M, N, K);
+                       (const float*)w, w_layout ? (int64_t)1 : (int64_t)N, w_layout ? (int64_t)K : (int64_t)1, (float*)y,
+                       ld_y, M, N, K);
     FLP_TRY_HIP(hipGetLastError());
     return FLP_OK;
   }
@@ -189,11 +192,12 @@ flp_status flp_launch_base_gemm(int dtype, const void* x, int64_t ld_x, const vo
     flp_set_error("base GEMM: d_in %d is not a multiple of %d", K, BK);
     return FLP_ENOTSUP;
   }
-  hipLaunchKernelGGL(transpose16_kernel, dim3((N + 63) / 64, (K + 63) / 64), dim3(256), 0, stream, (const uint16_t*)w,
-                     (uint16_t*)wt_scratch, K, N);
+  if (w_layout == 0)
+    hipLaunchKernelGGL(transpose16_kernel, dim3((N + 63) / 64, (K + 63) / 64), dim3(256), 0, stream, (const uint16_t*)w,
+                       (uint16_t*)wt_scratch, K, N);
   dim3 grid((N + BN - 1) / BN, (M + BM - 1) / BM);
   const uint16_t* xs = (const uint16_t*)x;
-  const uint16_t* ws = (const uint16_t*)wt_scratch;
+  const uint16_t* ws = w_layout == 0 ? (const uint16_t*)wt_scratch : (const uint16_t*)w;
   if (dtype == FLP_F16)
     hipLaunchKernelGGL(gemm_nt_kernel<GF16>, grid, dim3(256), 0, stream, xs, ld_x, ws, (uint16_t*)y, ld_y, y32, M, N, K);
   else

@@ -48,7 +48,7 @@ class AttnBatch(C.Structure):
 
 
 class LoraProj(C.Structure):
-    _fields_ = [("d_out", C.c_int32), ("reserved", C.c_int32), ("ld_y", C.c_int64), ("y", C.c_void_p),
+    _fields_ = [("d_out", C.c_int32), ("w_base_layout", C.c_int32), ("ld_y", C.c_int64), ("y", C.c_void_p),
                 ("w_base", C.c_void_p), ("a_tab_off", C.c_void_p), ("a_row_base", C.c_void_p),
                 ("b_tab_off", C.c_void_p), ("b_row_base", C.c_void_p)]
 

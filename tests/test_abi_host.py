@@ -40,6 +40,29 @@ def test_library_exports_every_declared_symbol():
     assert b"flpool" in lib.flp_version()
 
 
+def test_layer_header_symbols_and_structs():
+    from paper_2505_03756_amd import fllayer
+    lib = flpool.load()
+    header = open(os.path.join(ROOT, "include", "fllayer.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b(fll_[a-z_0-9]+)\s*\(", header))
+    assert declared == set(fllayer.EXPORTS)
+    for name in declared:
+        assert hasattr(lib, name), name
+    assert C.sizeof(fllayer.LayerConfig) == 24
+    assert C.sizeof(fllayer.LayerWeights) == 9 * 8
+    assert C.sizeof(fllayer.LoraPlace) == 32
+    assert C.sizeof(fllayer.LayerBatch) == 24 + 8 * 8 + 7 * 32
+    # argument checks that need no GPU
+    assert lib.fll_rmsnorm(1, None, None, None, 4, 64, C.c_float(1e-5), None) == flpool.FLP_EINVAL
+    assert lib.fll_rope(1, None, None, None, 4, 2, 2, 128, C.c_float(1e4), None) == flpool.FLP_EINVAL
+    buf = np.zeros(64, np.float32)
+    fllayer._lib()
+    assert lib.fll_rope(0, buf.ctypes.data, None, buf.ctypes.data, 1, 1, 1, 96, C.c_float(1e4), None) == flpool.FLP_ENOTSUP
+    assert lib.fll_silu_mul(1, buf.ctypes.data, 7, buf.ctypes.data, 7, buf.ctypes.data, 7, 1, 7, None) == flpool.FLP_ENOTSUP
+    assert lib.fll_rmsnorm(1, buf.ctypes.data, buf.ctypes.data, buf.ctypes.data, 0, 64, C.c_float(1e-5), None) == flpool.FLP_OK
+
+
 def test_struct_sizes_match_header_layout():
     # natural alignment of the C structs in include/flpool.h
     assert C.sizeof(flpool.PoolConfig) == 48
