@@ -51,6 +51,10 @@ def parse():
     ap.add_argument("--skew-std", type=float, default=None, help="x of skewed-x, in adapter ids")
     ap.add_argument("--seqs", type=int, default=None, help="override the number of sequences; the new-token range "
                     "is scaled so that the step keeps its token count")
+    ap.add_argument("--layers", type=int, default=2, help="decoder layers of the layer_stack section (0: skip); the "
+                    "stack runs the batch through that many layers with per-layer pools and random weights")
+    ap.add_argument("--mlp-dim", type=int, default=None, help="MLP width of the layer_stack section "
+                    "(default: the workload's, else 11008 for hidden 4096)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample")
     ap.add_argument("--seed", type=int, default=None)
@@ -357,10 +361,81 @@ def main():
         "with_base_gemm": base_info,
     }
 
+    if args.layers > 0 and cfg.dtype != "f32":
+        out["layer_stack"] = layer_stack(args, cfg, runners[0], s_comp)
     if not args.no_cpu_baseline:
         out["host_logic"] = host_logic()
         out["cpu_baseline"] = cpu_baseline(wl.make_step(cfg, seed=seed), args.cpu_seconds)
     print(json.dumps(out))
+
+
+def layer_stack(args, cfg, r0, stream):
+    """The batch through `--layers` whole decoder layers (include/fllayer.h): RMSNorm, dense base projections
+    with the paged LoRA branch, RoPE, KV append, paged prefix attention, gated-SiLU MLP, residuals; one pool
+    per layer (each a copy of the batch's pool: same block ids and tables in every layer), random weights of
+    the model's shapes.  All blocks are resident (the swap belongs to the headline figure, not to this one)."""
+    import numpy as np
+    import torch
+    from paper_2505_03756_amd import fllayer, flpool
+    g, step, T = r0.g, r0.step, r0.T
+    L = int(args.layers)
+    mlp = int(args.mlp_dim or cfg.mlp_dim or {4096: 11008, 5120: 13824, 8192: 22016}.get(cfg.hidden, 4 * cfg.hidden))
+    tdt = torch.float16 if cfg.dtype == "f16" else torch.bfloat16
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(20250611)
+    qd, kd = cfg.n_q_heads * cfg.head_dim, cfg.n_kv_heads * cfg.head_dim
+    shapes = {"q": (qd, cfg.hidden), "k": (kd, cfg.hidden), "v": (kd, cfg.hidden), "o": (cfg.hidden, qd),
+              "gate": (mlp, cfg.hidden), "up": (mlp, cfg.hidden), "down": (cfg.hidden, mlp)}
+    layers, keep = [], []
+    host_stub = torch.zeros(cfg.block_elems, dtype=torch.int16).pin_memory()
+    for l in range(L):
+        if l == 0:
+            pool = g.pool
+        else:                                   # this layer's pool: the same blocks at the same ids
+            dev = g.dev.clone()
+            pool = flpool.Pool(cfg.dtype, cfg.n_kv_heads, cfg.head_dim, dev.shape[0], 1, block_tokens=cfg.block_tokens,
+                               dev=dev, host=host_stub)
+            keep.append(dev)
+        W = {n: (torch.randn(sh, generator=gen, device="cuda", dtype=torch.float32) * sh[1] ** -0.5).to(tdt)
+             for n, sh in shapes.items()}
+        W["in_norm"] = (1 + 0.1 * torch.randn(cfg.hidden, generator=gen, device="cuda")).to(tdt)
+        W["post_norm"] = (1 + 0.1 * torch.randn(cfg.hidden, generator=gen, device="cuda")).to(tdt)
+        layers.append(fllayer.Layer(pool, cfg.hidden, cfg.n_q_heads, mlp, W))
+    pos = np.concatenate([step.prefix_len[i] + np.arange(step.cu_new[i + 1] - step.cu_new[i])
+                          for i in range(len(step.prefix_len))]).astype(np.int32)
+    places = {n: g.proj[n] for n in g.proj}
+    batch = fllayer.Batch(step.cu_new, step.prefix_len, torch.from_numpy(pos).cuda(), g.kv_tables, g.token_adapter,
+                          g.rank, g.scale, g.lora_tables, places, n_adapters=len(step.rank),
+                          max_rank=int(max(1, step.rank.max())), max_blocks_per_seq=step.kv_tables.shape[1])
+    nbytes = layers[0].scratch_bytes(T)
+    scratch = torch.empty(nbytes + 256, dtype=torch.uint8, device="cuda")
+    sp = (scratch.data_ptr() + 255) & ~255
+    h0 = torch.randn((T, cfg.hidden), generator=gen, device="cuda", dtype=torch.float32).to(tdt)
+    h = h0.clone()
+
+    def run():
+        h.copy_(h0)
+        for ly in layers:
+            ly.forward(batch, h, sp, nbytes, stream=stream)
+
+    with torch.cuda.stream(stream):
+        run()
+        torch.cuda.synchronize()
+        assert bool(torch.isfinite(h.float()).all()), "layer stack produced non-finite values"
+        reps = 3
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        for _ in range(reps):
+            run()
+        e1.record(stream)
+        torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / reps
+    gemm_flops = 2.0 * T * sum(a * b for a, b in shapes.values())
+    return {"layers": L, "mlp_dim": mlp, "tokens": T, "ms_stack": round(ms, 3), "ms_per_layer": round(ms / L, 3),
+            "tokens_per_s_per_layer": round(T / (ms / L * 1e-3), 1),
+            "dense_flops_per_layer": int(gemm_flops),
+            "dense_TFLOPps_if_all_time_were_gemm": round(gemm_flops * L / (ms * 1e9), 1),
+            "lora_on": sorted(places), "note": "blocks resident; random weights; one pool per layer"}
 
 
 def host_logic():

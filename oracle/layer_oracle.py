@@ -105,12 +105,15 @@ def layer_forward(cfg, step, pool, weights, h_storage, positions, eps=1e-5, thet
         out = {}
         xv = load(x_st, dt)
         for n in names:
-            pr = step.proj[n]
             base = xv @ W[n].T                                            # dense base, float64
-            zeros = np.zeros((T, pr.d_out), dtype=np.asarray(x_st).dtype)     # the oracle adds the branch to y_in
-            delta = _lora_apply(pool, dt, np.ascontiguousarray(x_st), step.token_adapter, step.rank, step.scale,
-                                pr.a_tab_off, pr.a_row_base, pr.b_tab_off, pr.b_row_base, step.lora_tables,
-                                pr.d_out, y_in=zeros)
+            pr = step.proj.get(n)
+            if pr is None:                                                # no LoRA on this projection
+                delta = 0.0
+            else:
+                zeros = np.zeros((T, pr.d_out), dtype=np.asarray(x_st).dtype)     # the oracle adds the branch to y_in
+                delta = _lora_apply(pool, dt, np.ascontiguousarray(x_st), step.token_adapter, step.rank, step.scale,
+                                    pr.a_tab_off, pr.a_row_base, pr.b_tab_off, pr.b_row_base, step.lora_tables,
+                                    pr.d_out, y_in=zeros)
             out[n], _ = round_store(base + delta, dt)
         return out
 

@@ -318,13 +318,25 @@ extern "C" flp_status fll_layer_forward(flp_pool* p, const fll_layer_config* c, 
     lb.rank = b->rank;
     lb.scale = b->scale;
     lb.block_tables = b->lora_tables;
+    int n_lora = 0;
     for (int i = 0; i < n_proj; ++i) {
       const fll_lora_place& pl = b->lora[which[i]];
-      if (!pl.a_tab_off || !pl.a_row_base || !pl.b_tab_off || !pl.b_row_base) {
-        flp_set_error("fll_layer_forward: projection %d has no LoRA placement", which[i]);
+      const int n_set = (pl.a_tab_off != nullptr) + (pl.a_row_base != nullptr) + (pl.b_tab_off != nullptr) +
+                        (pl.b_row_base != nullptr);
+      if (n_set == 0) {                               // no LoRA branch on this projection: the dense product alone
+        if (p->elem_bytes == 2 && d_in % 64) {
+          flp_set_error("fll_layer_forward: projection %d: d_in %d is not a multiple of 64", which[i], d_in);
+          return FLP_ENOTSUP;
+        }
+        FLP_TRY(flp_launch_base_gemm(dtype, x, d_in, ws[i], 1, ys[i], d_outs[i], T, d_outs[i], d_in, nullptr, nullptr,
+                                     (hipStream_t)hip_stream));
+        continue;
+      }
+      if (n_set != 4) {
+        flp_set_error("fll_layer_forward: projection %d has an incomplete LoRA placement", which[i]);
         return FLP_EINVAL;
       }
-      flp_lora_proj& pr = lb.proj[i];
+      flp_lora_proj& pr = lb.proj[n_lora++];
       pr.d_out = d_outs[i];
       pr.w_base_layout = 1;
       pr.ld_y = d_outs[i];
@@ -335,6 +347,8 @@ extern "C" flp_status fll_layer_forward(flp_pool* p, const fll_layer_config* c, 
       pr.b_tab_off = pl.b_tab_off;
       pr.b_row_base = pl.b_row_base;
     }
+    if (n_lora == 0) return FLP_OK;
+    lb.n_proj = n_lora;
     return flp_lora_apply_paged(p, &lb, hip_stream);
   };
 

@@ -132,6 +132,8 @@ LAYER_CASES = {
     "bf16_gqa_mixed": lambda: layer_cfg("bf16", n_q_heads=8, n_kv_heads=2, hidden=1024, decode_frac=0.5, seed=42),
     "f32_small": lambda: layer_cfg("f32", n_seqs=3, prefix_range=(0, 60), new_range=(1, 20), hidden=256, n_q_heads=2,
                                    n_kv_heads=2, mlp_dim=512, n_dev_blocks=300, seed=43),
+    # LoRA on the attention projections only (the 7B workload): the MLP projections are dense products alone
+    "bf16_attention_lora_only": lambda: layer_cfg("bf16", projections=("q", "k", "v", "o"), seed=45),
     # enough tokens for the matrix-core LoRA and attention kernels
     "f16_long": lambda: layer_cfg("f16", n_seqs=10, prefix_range=(0, 300), new_range=(100, 160), n_dev_blocks=2500, seed=44),
 }

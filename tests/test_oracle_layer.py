@@ -175,6 +175,16 @@ def test_layer_single_token_reduces_to_matrix_products():
     assert np.allclose(lo.load(inter["attn"], cfg.dtype), v, rtol=0, atol=1e-6)
 
 
+def test_layer_projection_without_placement_is_the_dense_product():
+    cfg = small_cfg(projections=("q", "k", "v", "o"))
+    step = wl.make_step(cfg)
+    W = make_weights(cfg, np.random.default_rng(9))
+    h0, _ = lo.round_store(np.random.default_rng(10).normal(0, 1, (step.n_tokens, cfg.hidden)), cfg.dtype)
+    _, a = lo.layer_forward(cfg, step, pool_image(step), W, h0, positions_of(step))
+    n2 = lo.load(a["n2"], cfg.dtype)
+    assert np.allclose(lo.load(a["up"], cfg.dtype), (n2 @ lo.load(W["up"], cfg.dtype).T).astype(np.float32), atol=1e-6)
+
+
 def test_layer_lora_branch_enters_every_projection():
     # doubling every adapter's scale changes each projection's output by exactly its LoRA branch
     cfg = small_cfg()
