@@ -18,6 +18,7 @@
 namespace {
 
 typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4g __attribute__((ext_vector_type(4)));
 typedef _Float16 h16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 b16x8 __attribute__((ext_vector_type(8)));
 
@@ -162,6 +163,194 @@ __global__ __launch_bounds__(256, 2) void gemm_nt_kernel(const uint16_t* __restr
   }
 }
 
+// ---- large batches: 256 x 256 output tile per workgroup, operands streamed by direct global-to-LDS loads
+//
+// Four waves, each a 128 x 128 corner (4 x 4 accumulators of mfma_f32_32x32x16: 256 accumulator registers,
+// one wave per SIMD), so that a k step of 16 costs 8 fragment reads for 16 MFMAs: LDS traffic per flop is
+// half that of a 64 x 64 corner, and the operand tiles are fetched from L2 half as often as with 128 x 128
+// workgroup tiles.  Operand tiles are 256 rows x 32 coefficients (16 KiB each) in a ring of four stages; tile
+// t + 3 is requested right after the barrier of tile t with global_load_lds_dwordx4 (no registers, no LDS
+// store instructions), written as inline assembly so that the compiler's own counter waits leave them alone;
+// the wave waits for all but the newest tile's loads before each barrier, so tiles t and t + 1 are complete
+// when tile t is multiplied and the fragments of the next step - also across the tile boundary - are read while
+// the current step's MFMAs run.  LDS layout: four 64-byte rows share a 256-byte line and the line's 16 slots
+// are XOR-ed with the line index, which makes the 16 lanes that read one 16-byte chunk of 16 consecutive rows
+// hit 16 different slots; the swizzle is applied on the global side (a lane fetches the chunk that belongs
+// at its fixed LDS slot).  Workgroups of one XCD (ids congruent modulo 8) cover 4 x 8 blocks of tiles, so
+// the 32 that run together fetch 12 operand panels instead of 64.
+constexpr int GT = 256, GK = 32, kGStage = 2 * GT * GK * 2, kGStages = 4;   // 32 KiB per stage
+constexpr int kGLoads = 8;                                                    // direct loads per wave and tile
+// s_waitcnt immediate (gfx9 encoding: vmcnt[3:0] + [15:14], expcnt[6:4], lgkmcnt[11:8]): vmcnt only
+constexpr int vmcnt_imm(int n) { return (n & 15) | ((n >> 4) << 14) | (7 << 4) | (15 << 8); }
+
+__device__ __forceinline__ void gload_lds16(const void* base, uint32_t voff, uint32_t lds) {
+  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(voff), "s"(base), "s"(lds)
+               : "memory");
+}
+typedef __attribute__((address_space(3))) uint8_t g_lds_u8;
+
+// byte offset of 16-byte chunk c (0..3) of row r (0..255) inside a 256 x 32 operand tile
+__device__ __forceinline__ int gtile_off(int r, int c) {
+  const int line = r >> 2;
+  return line * 256 + (((((r & 3) << 2) | c) ^ (line & 3)) << 4);
+}
+
+template <typename G>
+__global__ __launch_bounds__(256, 1) void gemm_nt256_kernel(const uint16_t* __restrict__ x, int64_t ld_x,
+                                                            const uint16_t* __restrict__ wt, uint16_t* __restrict__ y,
+                                                            int64_t ld_y, float* __restrict__ y32, int M, int N, int K,
+                                                            int tiles_n, int tiles_m, int groups_n) {
+  typedef typename G::vec vec;
+  __shared__ __attribute__((aligned(1024))) uint8_t smem[kGStages * kGStage];
+  const int tid = threadIdx.x, lane = tid & 63, lr = lane & 31, hf = lane >> 5;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wi = wave & 1, wj = wave >> 1;
+
+  // workgroup -> tile: 32 consecutive workgroups of one XCD form a block of 4 feature tiles x 8 token tiles
+  const int xcd = blockIdx.x & 7, l = blockIdx.x >> 3;
+  const int gid = (l >> 5) * 8 + xcd, within = l & 31;
+  const int tn = (gid % groups_n) * 4 + (within & 3), tm = (gid / groups_n) * 8 + (within >> 2);
+  if (tn >= tiles_n || tm >= tiles_m) return;
+  const int n0 = tn * GT, m0 = tm * GT;
+
+  // ---- staging: wave w moves lines 16w .. 16w+15 (rows 64w .. 64w+63) of both tiles, 4 lines per instruction
+  const int l4 = lane >> 4, slot = (lane & 15) ^ l4;          // the line index is congruent to l4 modulo 4
+  const int rr = 4 * l4 + (slot >> 2), sc = slot & 3;
+  uint32_t va[4], vb[4];
+#pragma unroll
+  for (int q = 0; q < 4; ++q) {
+    const int r = 64 * wave + 16 * q + rr;
+    const int n = n0 + r < N ? n0 + r : N - 1;                // clamped rows are never stored
+    const int m = m0 + r < M ? m0 + r : M - 1;
+    va[q] = (uint32_t)(((int64_t)n * K + 8 * sc) * 2);
+    vb[q] = (uint32_t)(((int64_t)m * ld_x + 8 * sc) * 2);
+  }
+  const uint32_t lds_wave = (uint32_t)(uintptr_t)(g_lds_u8*)smem + 4096u * (uint32_t)wave;
+  const int nk = K / GK;
+  // one of the 8 direct loads of tile t: q = 0..3 the W^T tile, q = 4..7 the token tile
+  auto issue_load = [&](int t, int q) {
+    const int tk = t < nk ? t : nk - 1;                       // past the end: the last tile again, into a free stage
+    const uint32_t dst = lds_wave + (uint32_t)(t & (kGStages - 1)) * kGStage;
+    if (q < 4)
+      gload_lds16(wt + (int64_t)tk * GK, va[q], dst + 1024 * q);
+    else
+      gload_lds16(x + (int64_t)tk * GK, vb[q - 4], dst + GT * GK * 2 + 1024 * (q - 4));
+  };
+
+  // ---- fragments: A operand = rows of W^T in the permuted order that gives a lane 16 consecutive output
+  //      columns (row a of a 32-row tile is column 16*((a>>2)&1) + 4*(a>>3) + (a&3)); B operand = token rows
+  const int acol = (((lr >> 2) & 1) << 4) | ((lr >> 3) << 2) | (lr & 3);
+  int offa[4], offb[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    offa[i] = gtile_off(128 * wi + 32 * i + acol, hf);
+    offb[i] = GT * GK * 2 + gtile_off(128 * wj + 32 * i + lr, hf);
+  }
+  // chunk 2*kk + hf of the row: bit 1 of the slot, bit 5 of the offset
+  auto frag = [&](int t, int kk, int off) {
+    return *reinterpret_cast<const vec*>(smem + (t & (kGStages - 1)) * kGStage + (off ^ (kk << 5)));
+  };
+
+  f32x16 acc[4][4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+
+#pragma unroll
+  for (int t = 0; t < kGStages - 1; ++t)
+#pragma unroll
+    for (int q = 0; q < 8; ++q) issue_load(t, q);
+
+  vec a0[4], b0[4], a1[4], b1[4];
+  for (int kt = 0; kt < nk; ++kt) {
+    // all but the newest tile's loads of this wave are complete, after the barrier everybody's: tiles kt and
+    // kt + 1 are in LDS; everybody is also done with tile kt - 1, whose stage takes tile kt + 3
+    __builtin_amdgcn_s_waitcnt(vmcnt_imm(kGLoads));
+    __syncthreads();
+    if (kt == 0) {
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        a0[i] = frag(0, 0, offa[i]);
+        b0[i] = frag(0, 0, offb[i]);
+      }
+    }
+    // The iteration is eight groups of {one direct load of tile kt + 3, the two fragment reads that the step
+    // after this one needs, four MFMAs}, fenced so that they stay in this order: a burst of eight loads at the
+    // top of the iteration holds the wave's in-order instruction stream (and with it the matrix pipe) for as
+    // long as the memory pipeline takes to accept them.
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {                             // k step 0 of tile kt; fetches k step 1
+      issue_load(kt + kGStages - 1, g);
+      if (g < 2) {                                            // all token fragments first: the next step's first group needs them
+        b1[2 * g] = frag(kt, 1, offb[2 * g]);
+        b1[2 * g + 1] = frag(kt, 1, offb[2 * g + 1]);
+      } else {
+        a1[2 * g - 4] = frag(kt, 1, offa[2 * g - 4]);
+        a1[2 * g - 3] = frag(kt, 1, offa[2 * g - 3]);
+      }
+#pragma unroll
+      for (int j = 0; j < 4; ++j) acc[g][j] = G::mfma(a0[g], b0[j], acc[g][j]);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {                             // k step 1 of tile kt; fetches k step 0 of tile kt + 1
+      issue_load(kt + kGStages - 1, 4 + g);
+      if (g < 2) {
+        b0[2 * g] = frag(kt + 1, 0, offb[2 * g]);
+        b0[2 * g + 1] = frag(kt + 1, 0, offb[2 * g + 1]);
+      } else {
+        a0[2 * g - 4] = frag(kt + 1, 0, offa[2 * g - 4]);
+        a0[2 * g - 3] = frag(kt + 1, 0, offa[2 * g - 3]);
+      }
+#pragma unroll
+      for (int j = 0; j < 4; ++j) acc[g][j] = G::mfma(a1[g], b1[j], acc[g][j]);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  }
+  __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));               // the look-ahead loads must land before the LDS is released
+
+  // lane (token lr of tile j, half hf) holds columns 16*hf .. 16*hf+15 of feature tile i
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    const int m = m0 + 128 * wj + 32 * j + lr;
+    if (m >= M) continue;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int n = n0 + 128 * wi + 32 * i + 16 * hf;
+      if (n >= N) continue;
+      if (y32) {
+        float* yp32 = y32 + (int64_t)m * N + n;
+        if (n + 16 <= N && (N & 3) == 0) {
+#pragma unroll
+          for (int e4 = 0; e4 < 4; ++e4) {
+            f32x4g v4 = {acc[i][j][4 * e4], acc[i][j][4 * e4 + 1], acc[i][j][4 * e4 + 2], acc[i][j][4 * e4 + 3]};
+            reinterpret_cast<f32x4g*>(yp32)[e4] = v4;
+          }
+        } else {
+          for (int e = 0; e < 16; ++e)
+            if (n + e < N) yp32[e] = acc[i][j][e];
+        }
+      }
+      uint16_t o[16];
+#pragma unroll
+      for (int e = 0; e < 16; ++e) o[e] = G::out(acc[i][j][e]);
+      uint16_t* yp = y + (int64_t)m * ld_y + n;
+      if (n + 16 <= N) {
+        u32x4 raw[2];
+        __builtin_memcpy(raw, o, 32);
+        reinterpret_cast<u32x4*>(yp)[0] = raw[0];
+        reinterpret_cast<u32x4*>(yp)[1] = raw[1];
+      } else {
+        for (int e = 0; e < 16; ++e)
+          if (n + e < N) yp[e] = o[e];
+      }
+    }
+  }
+}
+
 __global__ __launch_bounds__(256) void gemm_f32_kernel(const float* __restrict__ x, int64_t ld_x,
                                                        const float* __restrict__ w, int64_t w_k_stride,
                                                        int64_t w_n_stride, float* __restrict__ y, int64_t ld_y, int M,
@@ -195,9 +384,26 @@ flp_status flp_launch_base_gemm(int dtype, const void* x, int64_t ld_x, const vo
   if (w_layout == 0)
     hipLaunchKernelGGL(transpose16_kernel, dim3((N + 63) / 64, (K + 63) / 64), dim3(256), 0, stream, (const uint16_t*)w,
                        (uint16_t*)wt_scratch, K, N);
-  dim3 grid((N + BN - 1) / BN, (M + BM - 1) / BM);
   const uint16_t* xs = (const uint16_t*)x;
   const uint16_t* ws = w_layout == 0 ? (const uint16_t*)wt_scratch : (const uint16_t*)w;
+  // 32-bit byte offsets inside the operands and enough 256 x 256 tiles to occupy the chip (measured: with 64
+  // tiles the 128 x 128 kernel is ahead, from 172 tiles on this one): the 256 x 256 kernel
+  if (M >= 1024 && N >= 256 && (int64_t)((M + GT - 1) / GT) * ((N + GT - 1) / GT) >= 96 && (int64_t)M * ld_x * 2 < ((int64_t)1 << 32) && (int64_t)N * K * 2 < ((int64_t)1 << 32) &&
+      ld_x % 8 == 0 && K / GK >= kGStages) {
+    const int tiles_n = (N + GT - 1) / GT, tiles_m = (M + GT - 1) / GT;
+    const int groups_n = (tiles_n + 3) / 4, groups_m = (tiles_m + 7) / 8;
+    const int n_groups = (groups_n * groups_m + 7) / 8 * 8;
+    dim3 grid256((unsigned)(n_groups * 32));
+    if (dtype == FLP_F16)
+      hipLaunchKernelGGL(gemm_nt256_kernel<GF16>, grid256, dim3(256), 0, stream, xs, ld_x, ws, (uint16_t*)y, ld_y, y32, M,
+                         N, K, tiles_n, tiles_m, groups_n);
+    else
+      hipLaunchKernelGGL(gemm_nt256_kernel<GBF16>, grid256, dim3(256), 0, stream, xs, ld_x, ws, (uint16_t*)y, ld_y, y32,
+                         M, N, K, tiles_n, tiles_m, groups_n);
+    FLP_TRY_HIP(hipGetLastError());
+    return FLP_OK;
+  }
+  dim3 grid((N + BN - 1) / BN, (M + BM - 1) / BM);
   if (dtype == FLP_F16)
     hipLaunchKernelGGL(gemm_nt_kernel<GF16>, grid, dim3(256), 0, stream, xs, ld_x, ws, (uint16_t*)y, ld_y, y32, M, N, K);
   else

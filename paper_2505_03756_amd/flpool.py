@@ -210,7 +210,8 @@ class Pool:
 
     def lora_apply_paged(self, x, token_adapter, rank, scale, block_tables, projs: Sequence[dict], n_tokens, d_in,
                          n_adapters, max_rank, ld_x=None, stream=None):
-        """projs: dicts with y, d_out, a_tab_off, a_row_base, b_tab_off, b_row_base and optional ld_y, w_base."""
+        """projs: dicts with y, d_out, a_tab_off, a_row_base, b_tab_off, b_row_base and optional ld_y, w_base, w_base_layout
+        (0: w_base is [d_in, d_out]; 1: [d_out, d_in])."""
         if not 1 <= len(projs) <= MAX_PROJ:
             raise FlpError(FLP_EINVAL, "1..%d projections per call" % MAX_PROJ)
         b = LoraBatch()
@@ -223,6 +224,7 @@ class Pool:
             pr.d_out = int(p["d_out"])
             pr.ld_y = int(p.get("ld_y", p["d_out"]))
             pr.y, pr.w_base = _ptr(p["y"]), _ptr(p.get("w_base"))
+            pr.w_base_layout = int(p.get("w_base_layout", 0))
             pr.a_tab_off, pr.a_row_base = _ptr(p["a_tab_off"]), _ptr(p["a_row_base"])
             pr.b_tab_off, pr.b_row_base = _ptr(p["b_tab_off"]), _ptr(p["b_row_base"])
         _check(self._lib.flp_lora_apply_paged(self._h, C.byref(b), _stream(stream)))

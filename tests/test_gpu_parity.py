@@ -152,6 +152,10 @@ LORA_CASES = {
                                                  prefix_range=(0, 0), new_range=(1, 1), decode_frac=1.0,
                                                  n_adapters=1000, ranks=(16, 32), adapter_dist="skewed", skew_std=12.0,
                                                  n_dev_blocks=6000, swap_in_frac=0.0, seed=87),
+    # over 1024 tokens with output widths that are not multiples of the large GEMM tile (q, o: 320 of 256; k, v: 64)
+    "bf16_dense_tail": lambda: small_cfg("bf16", hidden=320, n_q_heads=5, n_kv_heads=1, head_dim=64, n_seqs=20,
+                                         prefix_range=(0, 0), new_range=(40, 80), n_adapters=4, ranks=(16,),
+                                         n_dev_blocks=1200, swap_in_frac=0.0, seed=88),
     "f16_rank64_gqa": lambda: small_cfg("f16", hidden=1024, n_q_heads=8, n_kv_heads=2, n_seqs=30,
                                         prefix_range=(0, 0), new_range=(30, 120), n_adapters=5, ranks=(64,),
                                         n_dev_blocks=1500, swap_in_frac=0.0, seed=84),
@@ -182,7 +186,7 @@ def test_lora_matrix_core_shapes(name):
         assert err.max() <= ulp * (np.abs(want).max() + 1.0), (n, err.max())
 
 
-@pytest.mark.parametrize("name", ["tiny", "f16_prefill", "bf16_gqa_mixed", "f16_long_segments"])
+@pytest.mark.parametrize("name", ["tiny", "f16_prefill", "bf16_gqa_mixed", "f16_long_segments", "bf16_dense_tail"])
 def test_lora_with_dense_base(name):
     """w_base given: y = x.W_base + delta, the library computes the base term itself (Eq. 1's W)."""
     cfg = (CASES.get(name) or LORA_CASES[name])()
