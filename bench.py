@@ -49,6 +49,8 @@ def parse():
     ap.add_argument("--adapter-dist", default=None, choices=["uniform", "zipf", "distinct", "skewed"],
                     help="override how sequences pick their adapter (section 6.9: uniform, distinct, skewed-x)")
     ap.add_argument("--skew-std", type=float, default=None, help="x of skewed-x, in adapter ids")
+    ap.add_argument("--block-tokens", type=int, default=None, choices=[16, 32], help="token positions per pool block "
+                    "(32: the block size of the paper's vLLM baseline, as a layout variant; the pool keeps its bytes)")
     ap.add_argument("--seqs", type=int, default=None, help="override the number of sequences; the new-token range "
                     "is scaled so that the step keeps its token count")
     ap.add_argument("--layers", type=int, default=2, help="decoder layers of the layer_stack section (0: skip); the "
@@ -90,6 +92,11 @@ def main():
         over["adapter_dist"] = args.adapter_dist
     if args.skew_std is not None:
         over["skew_std"] = float(args.skew_std)
+    if args.block_tokens is not None and args.block_tokens != cfg.block_tokens:
+        f = args.block_tokens / float(cfg.block_tokens)
+        over["block_tokens"] = int(args.block_tokens)
+        over["n_dev_blocks"] = int(cfg.n_dev_blocks / f)
+        over["n_host_blocks"] = int(cfg.n_host_blocks / f)
     if args.seqs is not None and args.seqs != cfg.n_seqs:
         f = cfg.n_seqs / float(args.seqs)
         over["n_seqs"] = int(args.seqs)

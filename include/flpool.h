@@ -27,7 +27,8 @@
  *   BLOCK_ELEMS = 2 * block_tokens * n_kv_heads * head_dim.
  *   KV block:   K of (kv head g, slot s, channel c) at ((g*bt + s)*d + c),
  *               V of the same at n_kv*bt*d + ((g*d + c)*bt + s)   (V transposed,
- *               so 16 consecutive positions of one channel are contiguous).
+ *               so the bt positions of one channel are contiguous; the kernels work
+ *               on groups of 16 positions, one or two per block).
  *   LoRA block: page-rows of `row_len` elements packed from the start of the
  *               block, floor(BLOCK_ELEMS / row_len) rows per block, never
  *               straddling blocks (partition along the rank dimension, section
@@ -65,7 +66,7 @@ typedef int32_t flp_status;
 
 typedef struct {
   int32_t dtype;            /* FLP_F32 / FLP_F16 / FLP_BF16                                   */
-  int32_t block_tokens;     /* token positions per KV block (kernels support 16)              */
+  int32_t block_tokens;     /* token positions per KV block (kernels support 16 and 32)       */
   int32_t n_kv_heads;
   int32_t head_dim;         /* kernels support 64 and 128                                     */
   int64_t n_dev_blocks;

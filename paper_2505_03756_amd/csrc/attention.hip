@@ -6,8 +6,8 @@
 // query head h, softmax over positions 0..p of sm_scale * q.K, times V, with K and V read
 // through the sequence's block table.
 //
-// Block layout used here: K of (kv head g, slot s, channel c) at ((g*16 + s)*D + c); V of
-// the same at n_kv*16*D + ((g*D + c)*16 + s).  V is stored transposed so that the 16
+// Block layout used here, bt = 16 or 32 positions per block: K of (kv head g, slot s, channel c) at
+// ((g*bt + s)*D + c); V of the same at n_kv*bt*D + ((g*D + c)*bt + s).  V is stored transposed so that the 16
 // positions of one channel are one contiguous run: a lane that owns a channel reads them
 // with one or two 16-byte loads and accumulates P.V without any cross-lane traffic.
 #include <hip/hip_runtime.h>
@@ -17,7 +17,7 @@
 
 namespace {
 
-constexpr int BT = 16;   // token positions per block
+constexpr int BT = 16;   // token positions per group: a block holds one (block size 16) or two (32) groups
 
 // ------------------------------------------------------------------------------- append
 // One workgroup per (sequence, block, 256 vector-columns) unit.  A thread owns 16 bytes of a
@@ -43,15 +43,21 @@ __global__ __launch_bounds__(256, 2) void kv_append_kernel(FlpAttnArgs a, const 
   const bool valid = e0 < row;
   const int ns = u.s1 - u.s0;
   const bool full = ns == BT;
-  const int64_t blk = a.tables[(int64_t)u.seq * a.max_blocks + u.blk_idx];
+  const int bt = a.bt, hpb = bt / BT, half = u.blk_idx % hpb;       // the unit is group `half` of its block
+  const int64_t blk = a.tables[(int64_t)u.seq * a.max_blocks + u.blk_idx / hpb];
   S* __restrict__ base = reinterpret_cast<S*>(a.pool) + blk * a.block_elems;
-  // V of the unit's 256 threads is 64 KiB contiguous in the block, thread t owning bytes 256 t ...
-  u32x4* __restrict__ vdst = reinterpret_cast<u32x4*>(base + (int64_t)a.n_kv * BT * D + (int64_t)blockIdx.y * 256 * EPV * BT);
+  // 16-byte piece p = 16 t + VPR c + v of the unit's V: thread t (of this grid row), its channel c, vector v of
+  // the channel's 16-slot run.  With 16-position blocks the 4096 pieces are 64 KiB contiguous (thread t owns
+  // bytes 256 t ...); with 32-position blocks a run is one half of a 32-slot row.
+  S* __restrict__ vbase = base + (int64_t)a.n_kv * bt * D + (int64_t)blockIdx.y * 256 * EPV * bt + BT * half;
+  auto vpiece = [&](int piece) {
+    return reinterpret_cast<u32x4*>(vbase + (int64_t)(piece / VPR) * bt + (piece % VPR) * EPV);
+  };
   if (valid) {
     const S* __restrict__ kn = reinterpret_cast<const S*>(a.k_new) + (int64_t)u.t_first * row + e0;
     const S* __restrict__ vn = reinterpret_cast<const S*>(a.v_new) + (int64_t)u.t_first * row + e0;
     const int g = e0 / D, c0 = e0 - g * D;
-    S* __restrict__ kdst = base + ((int64_t)g * BT + u.s0) * D + c0;
+    S* __restrict__ kdst = base + ((int64_t)g * bt + BT * half + u.s0) * D + c0;
     u32x4 vv[BT];
     if (full) {
 #pragma unroll
@@ -91,7 +97,7 @@ __global__ __launch_bounds__(256, 2) void kv_append_kernel(FlpAttnArgs a, const 
         constexpr int SPW = 4 / (int)sizeof(S);
 #pragma unroll
         for (int v = 0; v < VPR; ++v) {
-          const u32x4 old = vdst[tid * UPT + c * VPR + v];
+          const u32x4 old = *vpiece(tid * UPT + c * VPR + v);
 #pragma unroll
           for (int w = 0; w < 4; ++w) {
             uint32_t mask = 0;
@@ -113,8 +119,13 @@ __global__ __launch_bounds__(256, 2) void kv_append_kernel(FlpAttnArgs a, const 
 #pragma unroll
   for (int j = 0; j < UPT; ++j) {
     const int owner = 16 * j + (tid >> 4), piece = tid & 15;
-    if ((blockIdx.y * 256 + owner) * EPV < row)
-      __builtin_nontemporal_store(tr[owner * UPT + (piece ^ (owner & 15))], vdst + 256 * j + tid);
+    if ((blockIdx.y * 256 + owner) * EPV < row) {
+      const u32x4 val = tr[owner * UPT + (piece ^ (owner & 15))];
+      if (hpb == 1)
+        __builtin_nontemporal_store(val, vpiece(256 * j + tid));   // whole lines: streaming stores pay
+      else
+        *vpiece(256 * j + tid) = val;                              // half lines of 32-slot rows: plain stores
+    }
   }
 }
 
@@ -149,7 +160,8 @@ __global__ __launch_bounds__(256) void attn_rows_kernel(FlpAttnArgs a, const Flp
   const ST* __restrict__ pool = reinterpret_cast<const ST*>(a.pool);
   const int ck = lane % C::LPK;     // which 16-byte chunk of a key row this lane reads
   const int kg = lane / C::LPK;     // which key of a wave-wide load this lane works on
-  const int64_t v_region = (int64_t)a.n_kv * BT * D;
+  const int bt = a.bt, hpb = bt / BT;
+  const int64_t v_region = (int64_t)a.n_kv * bt * D;
 
   for (int jj = 0; jj < u.n_tok; ++jj) {
     const int j = u.j0 + jj;
@@ -171,13 +183,15 @@ __global__ __launch_bounds__(256) void attn_rows_kernel(FlpAttnArgs a, const Flp
 
     const int nblk = (ctx + BT - 1) / BT;
     for (int b = 0; b < nblk; ++b) {
-      const ST* __restrict__ base = pool + (int64_t)table[b] * a.block_elems;
-      // ---- scores of the block's 16 keys
+      // group b of 16 positions: group b % hpb of block b / hpb
+      const ST* __restrict__ base = pool + (int64_t)table[b / hpb] * a.block_elems + BT * (b % hpb) * D;
+      const ST* __restrict__ vbase = pool + (int64_t)table[b / hpb] * a.block_elems + v_region + BT * (b % hpb);
+      // ---- scores of the group's 16 keys
       float s[C::NLD];
 #pragma unroll
       for (int i = 0; i < C::NLD; ++i) {
         const int key = i * C::KPL + kg;
-        u32x4 raw = *reinterpret_cast<const u32x4*>(base + ((int64_t)g * BT + key) * D + ck * C::EPL);
+        u32x4 raw = *reinterpret_cast<const u32x4*>(base + ((int64_t)g * bt + key) * D + ck * C::EPL);
         ST tmp[C::EPL];
         __builtin_memcpy(tmp, &raw, 16);
         float d = 0.f;
@@ -212,7 +226,7 @@ __global__ __launch_bounds__(256) void attn_rows_kernel(FlpAttnArgs a, const Flp
       // ---- P.V: this lane's channels, 16 positions each
 #pragma unroll
       for (int c = 0; c < C::CPL; ++c) {
-        const ST* vp = base + v_region + ((int64_t)g * D + (lane + 64 * c)) * BT;
+        const ST* vp = vbase + ((int64_t)g * D + (lane + 64 * c)) * bt;
         ST vv[BT];
         u32x4 raw[C::VLD];
 #pragma unroll

@@ -125,7 +125,9 @@ __global__ __launch_bounds__(512, 2) void attn_mfma_kernel(FlpAttnArgs a, const 
   const int t0 = a.cu_new[it.seq];
   const int N = a.cu_new[it.seq + 1] - t0;
   const int L = P + N;
-  const int nblk_valid = (L + BT - 1) / BT;
+  const int bt = a.bt, hpb = bt / BT;                 // a block holds one or two groups of 16 positions
+  const int ngrp_valid = (L + BT - 1) / BT;           // groups of 16 positions that hold keys of this sequence
+  const int nblk_valid = (L + bt - 1) / bt;
   const int32_t* __restrict__ table = a.tables + (int64_t)it.seq * a.max_blocks;
   const uint16_t* __restrict__ pool = reinterpret_cast<const uint16_t*>(a.pool);
   const float c = a.scale_log2e;
@@ -170,27 +172,29 @@ __global__ __launch_bounds__(512, 2) void attn_mfma_kernel(FlpAttnArgs a, const 
     const int key = ci >> 4;
     kg[j] = (uint32_t)(2 * (key * D + 8 * ((ci & 15) ^ k_swz(key))));
     const int vd = ci >> 1;
-    vg[j] = (uint32_t)(2 * (8 * (2 * vd + ((ci & 1) ^ v_swz(vd)))));
+    vg[j] = (uint32_t)(2 * (vd * bt + 8 * ((ci & 1) ^ v_swz(vd))));     // channel vd's run of 16 slots inside its bt-slot row
   }
-  const int64_t k_region = (int64_t)g * BT * D;
-  const int64_t v_region = (int64_t)a.n_kv * BT * D + (int64_t)g * D * BT;
+  const int64_t k_region = (int64_t)g * bt * D;
+  const int64_t v_region = (int64_t)a.n_kv * bt * D + (int64_t)g * D * bt;
   const uint32_t lds_wave = (uint32_t)(uintptr_t)(lds_u8*)smem + sblk * 4096 + 2 * (wave & 1) * 1024;   // LDS address of this wave's first quarter in stage 0
 
   for (int i = tid; i < nblk_valid; i += 512) tab_lds[i] = table[i];
   __builtin_amdgcn_s_waitcnt(kWaitVm0);                // the query fragments are in: from here on only tile loads are in flight
   __syncthreads();
-  auto block_id = [&](int t) {                       // id of this wave's block of tile t (clamped: always valid)
-    int bi = 4 * t + sblk;
-    bi = bi < nblk_valid ? bi : nblk_valid - 1;
-    return __builtin_amdgcn_readfirstlane(tab_lds[bi]);
+  // this wave's 16-position group of tile t (clamped: always valid), as block id * 2 + group inside the block
+  auto block_id = [&](int t) {
+    int gi = 4 * t + sblk;
+    gi = gi < ngrp_valid ? gi : ngrp_valid - 1;
+    return __builtin_amdgcn_readfirstlane(tab_lds[gi / hpb] * 2 + gi % hpb);
   };
   auto issue_tile = [&](int t, int32_t id) {         // 4 direct loads: tile t -> stage t % kStages
-    const uint16_t* blk = pool + (int64_t)id * a.block_elems;
+    const int half = id & 1;
+    const uint16_t* blk = pool + (int64_t)(id >> 1) * a.block_elems;
     const uint32_t dst = lds_wave + (t % kStages) * kStage;
 #pragma unroll
     for (int j = 0; j < 2; ++j) {
-      load_to_lds16(blk + k_region, kg[j], dst + j * 1024);
-      load_to_lds16(blk + v_region, vg[j], dst + kTile + j * 1024);
+      load_to_lds16(blk + k_region + BT * half * D, kg[j], dst + j * 1024);
+      load_to_lds16(blk + v_region + BT * half, vg[j], dst + kTile + j * 1024);
     }
   };
 

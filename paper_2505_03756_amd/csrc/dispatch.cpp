@@ -20,8 +20,8 @@ flp_status check_attn_batch(const flp_pool* p, const flp_attn_batch* b, bool nee
     flp_set_error("%s: bad sequence arrays", who);
     return FLP_EINVAL;
   }
-  if (p->cfg.block_tokens != 16 || (p->cfg.head_dim != 64 && p->cfg.head_dim != 128)) {
-    flp_set_error("%s: kernels support block_tokens 16 and head_dim 64/128 (pool has %d / %d)", who,
+  if ((p->cfg.block_tokens != 16 && p->cfg.block_tokens != 32) || (p->cfg.head_dim != 64 && p->cfg.head_dim != 128)) {
+    flp_set_error("%s: kernels support block_tokens 16 or 32 and head_dim 64/128 (pool has %d / %d)", who,
                   p->cfg.block_tokens, p->cfg.head_dim);
     return FLP_ENOTSUP;
   }
@@ -96,6 +96,7 @@ FlpAttnArgs make_args(const flp_pool* p, const flp_attn_batch* b, const StagedSe
   a.max_blocks = b->max_blocks_per_seq;
   a.n_h = b->n_q_heads;
   a.n_kv = p->cfg.n_kv_heads;
+  a.bt = p->cfg.block_tokens;
   a.q = b->q;
   a.out = b->out;
   a.k_new = b->k_new;
@@ -108,7 +109,7 @@ FlpAttnArgs make_args(const flp_pool* p, const flp_attn_batch* b, const StagedSe
 }
 
 flp_status append_locked(flp_pool* p, const flp_attn_batch* b, hipStream_t stream) {
-  const int bt = p->cfg.block_tokens;
+  const int bt = 16;                                 // the kernel's unit is a group of 16 positions, whatever the block size
   std::vector<FlpAppendUnit> units;
   for (int32_t i = 0; i < b->n_seqs; ++i) {
     const int32_t P = b->prefix_len[i], n = b->cu_new[i + 1] - b->cu_new[i];

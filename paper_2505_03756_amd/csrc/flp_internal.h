@@ -81,7 +81,9 @@ flp_status flp_launch_copy_blocks(const uint8_t* src_base, uint8_t* dst_base, co
 
 flp_status flp_launch_stage_copy(const void* src_pinned, void* dst_dev, size_t bytes, hipStream_t stream);
 
-struct FlpAppendUnit {   // the slots [s0, s1) of block `blk_idx` of sequence `seq`
+// Kernels work on groups of 16 token positions; a block of 32 positions is two such groups (group index
+// gi = position / 16 lives in block gi / (bt / 16), at slots 16 * (gi % (bt / 16)) ...).
+struct FlpAppendUnit {   // the slots [s0, s1) of the 16-position group `blk_idx` of sequence `seq`
   int32_t seq, blk_idx, s0, s1, t_first, pad0, pad1, pad2;
 };
 struct FlpAttnUnit {     // new tokens [j0, j0+n_tok) of sequence `seq`
@@ -98,6 +100,7 @@ struct FlpAttnArgs {
   const int32_t* tables;
   int32_t max_blocks;
   int32_t n_h, n_kv;
+  int32_t bt;                  // token positions per block: 16 or 32
   const void* q;
   void* out;
   const void* k_new;

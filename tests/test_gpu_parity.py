@@ -27,6 +27,15 @@ CASES = {
                                         prefix_range=(0, 500), seed=79),
     "f16_d64": lambda: small_cfg("f16", head_dim=64, n_q_heads=8, n_kv_heads=8, seed=80),
     "f32_d128": lambda: small_cfg("f32", n_seqs=4, prefix_range=(0, 120), new_range=(1, 40), seed=81),
+    # blocks of 32 token positions (the block size of the paper's vLLM baseline, section 2.2) as a layout variant:
+    # prefill on the matrix-core kernel, decode / mixed and fp32 on the row kernel, head_dim 64
+    "f16_prefill_bt32": lambda: small_cfg("f16", block_tokens=32, seed=91),
+    "bf16_gqa_mixed_bt32": lambda: small_cfg("bf16", block_tokens=32, n_q_heads=8, n_kv_heads=2, hidden=1024,
+                                             decode_frac=0.5, prefix_range=(0, 500), seed=92),
+    "bf16_decode_bt32": lambda: small_cfg("bf16", block_tokens=32, n_seqs=19, prefix_range=(1, 700), new_range=(1, 1),
+                                          decode_frac=1.0, n_dev_blocks=1200, seed=93),
+    "f32_d64_bt32": lambda: small_cfg("f32", block_tokens=32, head_dim=64, n_q_heads=8, n_kv_heads=8, n_seqs=4,
+                                      prefix_range=(0, 120), new_range=(1, 40), seed=94),
 }
 
 
