@@ -51,6 +51,10 @@ def parse():
     ap.add_argument("--skew-std", type=float, default=None, help="x of skewed-x, in adapter ids")
     ap.add_argument("--block-tokens", type=int, default=None, choices=[16, 32], help="token positions per pool block "
                     "(32: the block size of the paper's vLLM baseline, as a layout variant; the pool keeps its bytes)")
+    ap.add_argument("--dev-blocks", type=int, default=None, help="override the pool's device block count (the 13b and "
+                    "34b_gqa workloads name pools of 200-250 GB; a smaller pool that still holds the batch lets their "
+                    "shapes be timed, several layers deep)")
+    ap.add_argument("--host-blocks", type=int, default=None)
     ap.add_argument("--seqs", type=int, default=None, help="override the number of sequences; the new-token range "
                     "is scaled so that the step keeps its token count")
     ap.add_argument("--layers", type=int, default=2, help="decoder layers of the layer_stack section (0: skip); the "
@@ -97,6 +101,10 @@ def main():
         over["block_tokens"] = int(args.block_tokens)
         over["n_dev_blocks"] = int(cfg.n_dev_blocks / f)
         over["n_host_blocks"] = int(cfg.n_host_blocks / f)
+    if args.dev_blocks is not None:
+        over["n_dev_blocks"] = int(args.dev_blocks)
+    if args.host_blocks is not None:
+        over["n_host_blocks"] = int(args.host_blocks)
     if args.seqs is not None and args.seqs != cfg.n_seqs:
         f = cfg.n_seqs / float(args.seqs)
         over["n_seqs"] = int(args.seqs)
@@ -106,8 +114,9 @@ def main():
     if over:
         cfg = cfg.scaled(**over)
     if cfg.n_dev_blocks * cfg.block_bytes > 200 * 2 ** 30:
-        raise SystemExit("workload %s is a parity-test shape; this bench runs 7b_prefill or 7b_decode"
-                         % args.workload)
+        raise SystemExit("workload %s names a pool of %d GiB, a parity-test shape; time its kernels in a pool that "
+                         "just holds the batch with --dev-blocks N (and --host-blocks)"
+                         % (args.workload, cfg.n_dev_blocks * cfg.block_bytes >> 30))
     seed = cfg.seed if args.seed is None else args.seed
     t0 = time.time()
 
@@ -425,6 +434,7 @@ def layer_stack(args, cfg, r0, stream):
         for ly in layers:
             ly.forward(batch, h, sp, nbytes, stream=stream)
 
+    torch.cuda.synchronize()            # pools and weights were filled on torch's default stream
     with torch.cuda.stream(stream):
         run()
         torch.cuda.synchronize()
