@@ -72,9 +72,14 @@ __device__ __forceinline__ int find_segment(const int32_t* __restrict__ tile_sta
 }
 
 // ------------------------------------------------------------------------------- shrink
-template <typename L, int MT, int NT>
+// ONEP: a workgroup takes ONE projection of its tile (the grid grows by the number of projections): with
+// rank tiles NT >= 2 the accumulators and operand fragments of three projections at once leave one
+// wave per SIMD, and the kernel, which lives on loads in flight, then runs at a fraction of HBM rate; x is
+// re-read per projection, from L2.
+template <typename L, int MT, int NT, bool ONEP>
 __global__ __launch_bounds__(256) void lora_shrink_mfma_kernel(FlpLoraArgs a, FlpLoraMfma c) {
   typedef typename L::vec vec;
+  constexpr int NPJ = ONEP ? 1 : FLP_MAX_PROJ;         // projections held by this workgroup
   extern __shared__ float red[];                       // [4 waves][n_acc][64 lanes]
   // Each XCD (workgroups are placed on the 8 XCDs round-robin by their linear id) takes a contiguous
   // eighth of the tiles with all their k splits: tiles of one adapter are neighbours, so its A pages
@@ -83,11 +88,14 @@ __global__ __launch_bounds__(256) void lora_shrink_mfma_kernel(FlpLoraArgs a, Fl
   const int n_seg = *a.n_seg;
   const int n_tiles = a.tile_start[n_seg];
   const int per_xcd = (n_tiles + 7) / 8;
-  const int ks = (blockIdx.x >> 3) % c.k_splits;
+  const int per_tile = c.k_splits * (ONEP ? a.n_proj : 1);          // workgroups per tile
+  const int ks = ((blockIdx.x >> 3) % per_tile) / (ONEP ? a.n_proj : 1);
+  const int p_first = ONEP ? ((blockIdx.x >> 3) % per_tile) % a.n_proj : 0;   // local projection q is p_first + q
+  const int n_pl = ONEP ? 1 : a.n_proj;
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, row = lane & 15, kg = lane >> 4;
   const uint16_t* __restrict__ pool = reinterpret_cast<const uint16_t*>(a.pool);
   const int rpb = (int)(a.block_elems / a.d_in);
-  for (int lt = (blockIdx.x >> 3) / c.k_splits; lt < per_xcd; lt += (gridDim.x >> 3) / c.k_splits) {
+  for (int lt = (blockIdx.x >> 3) / per_tile; lt < per_xcd; lt += (gridDim.x >> 3) / per_tile) {
   const int tile = (blockIdx.x & 7) * per_xcd + lt;
   if (tile >= n_tiles) break;
   const int s = find_segment(a.tile_start, n_seg, tile);
@@ -104,27 +112,28 @@ __global__ __launch_bounds__(256) void lora_shrink_mfma_kernel(FlpLoraArgs a, Fl
     pos = pos < pos_end ? pos : pos_end - 1;           // padding rows repeat the last token
     xp[mt] = reinterpret_cast<const uint16_t*>(a.x) + (int64_t)a.perm[pos] * a.ld_x + 8 * kg;
   }
-  const uint16_t* ap[FLP_MAX_PROJ][NT];
+  const uint16_t* ap[NPJ][NT];
   bool avalid[NT];
 #pragma unroll
   for (int nt = 0; nt < NT; ++nt) avalid[nt] = 16 * nt + row < r;
 #pragma unroll
-  for (int p = 0; p < FLP_MAX_PROJ; ++p)
+  for (int p = 0; p < NPJ; ++p)
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt) {
       ap[p][nt] = pool;
-      if (p < a.n_proj && r > 0) {
-        const int i = a.proj[p].a_row_base[ad] + (avalid[nt] ? 16 * nt + row : 0);
-        ap[p][nt] = pool + (int64_t)a.tables[a.proj[p].a_tab_off[ad] + i / rpb] * a.block_elems +
+      if (p < n_pl && r > 0) {
+        const flp_lora_proj& pr = a.proj[p_first + p];
+        const int i = pr.a_row_base[ad] + (avalid[nt] ? 16 * nt + row : 0);
+        ap[p][nt] = pool + (int64_t)a.tables[pr.a_tab_off[ad] + i / rpb] * a.block_elems +
                     (int64_t)(i % rpb) * a.d_in + 8 * kg;
       }
     }
 
-  f32x4 acc[MT][FLP_MAX_PROJ][NT];
+  f32x4 acc[MT][NPJ][NT];
 #pragma unroll
   for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
-    for (int p = 0; p < FLP_MAX_PROJ; ++p)
+    for (int p = 0; p < NPJ; ++p)
 #pragma unroll
       for (int nt = 0; nt < NT; ++nt) acc[mt][p][nt] = f32x4{0.f, 0.f, 0.f, 0.f};
 
@@ -136,8 +145,8 @@ __global__ __launch_bounds__(256) void lora_shrink_mfma_kernel(FlpLoraArgs a, Fl
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) xf[mt] = vec_from<vec>(*reinterpret_cast<const u32x4*>(xp[mt] + c0));
 #pragma unroll
-    for (int p = 0; p < FLP_MAX_PROJ; ++p) {
-      if (p < a.n_proj) {
+    for (int p = 0; p < NPJ; ++p) {
+      if (p < n_pl) {
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) {
           if (16 * nt < r) {
@@ -152,26 +161,26 @@ __global__ __launch_bounds__(256) void lora_shrink_mfma_kernel(FlpLoraArgs a, Fl
   }
 
   // ---- sum the four waves' partial tiles in a fixed order, then store
-  const int n_acc = MT * a.n_proj * NT * 4;
+  const int n_acc = MT * n_pl * NT * 4;
 #pragma unroll
   for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
-    for (int p = 0; p < FLP_MAX_PROJ; ++p)
-      if (p < a.n_proj)
+    for (int p = 0; p < NPJ; ++p)
+      if (p < n_pl)
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt)
 #pragma unroll
           for (int i = 0; i < 4; ++i)
-            red[(wave * n_acc + ((mt * a.n_proj + p) * NT + nt) * 4 + i) * 64 + lane] = acc[mt][p][nt][i];
+            red[(wave * n_acc + ((mt * n_pl + p) * NT + nt) * 4 + i) * 64 + lane] = acc[mt][p][nt][i];
   __syncthreads();
   const int RP = 16 * NT;
   float* __restrict__ vout = a.v + ((int64_t)ks * c.v_rows + (int64_t)tile * TM) * a.n_proj * RP;
   for (int e = tid; e < n_acc * 64; e += 256) {
     const float sum = ((red[e] + red[n_acc * 64 + e]) + red[2 * n_acc * 64 + e]) + red[3 * n_acc * 64 + e];
     const int ln = e & 63, q = e >> 6;
-    const int i = q & 3, nt = (q >> 2) % NT, p = ((q >> 2) / NT) % a.n_proj, mt = (q >> 2) / (NT * a.n_proj);
+    const int i = q & 3, nt = (q >> 2) % NT, p = ((q >> 2) / NT) % n_pl, mt = (q >> 2) / (NT * n_pl);
     const int trow = 16 * mt + (ln >> 4) * 4 + i, rho = 16 * nt + (ln & 15);
-    vout[((int64_t)trow * a.n_proj + p) * RP + rho] = sum;
+    vout[((int64_t)trow * a.n_proj + p_first + p) * RP + rho] = sum;
   }
   __syncthreads();                                     // the next tile reuses the reduction buffer
   }
@@ -345,17 +354,168 @@ __global__ __launch_bounds__(64) void lora_expand_mfma_kernel(FlpLoraArgs a, Flp
   }
 }
 
+// ------------------------------------------------------------------------------- expand, ranks above 16
+// With 2 or 4 rank tiles the register-resident fragments of the kernel above cover only 64-128 columns
+// per gather, and every such piece re-reads the tokens' v rows (which grow with the rank as well): at rank
+// 64 it runs at a seventh of the y stream's rate.  Here a workgroup of four waves owns one (tile group,
+// 256-column slab, projection): the slab's B coefficients (up to 64 ranks x 256 columns) are read once,
+// coalesced, and laid out in LDS transposed - [column][rank], 128 bytes per column - so that a lane's
+// A-operand fragment (8 consecutive ranks of one column) is one 16-byte LDS read; each wave then takes
+// every fourth 16-token sub-tile: v is loaded and split once per sub-tile for all 256 columns, and per
+// 64-column chunk the wave reads y, 4 x NT fragments from LDS, multiplies and writes y back.
+// LDS slot s (16 bytes: rank tile s / 2, half s % 2) of column c sits at c * 128 + ((s ^ f(c)) * 16) with
+// f(c) = (c & 3) | ((c >> 4) & 1) << 2: the 8 lanes that read one slot of 8 different columns (the
+// interleaved column order of the product) hit 8 different 16-byte bank groups.
+template <typename L, int NT>
+__global__ __launch_bounds__(256) void lora_expand_lds_kernel(FlpLoraArgs a, FlpLoraMfma c) {
+  typedef typename L::vec vec;
+  typedef typename L::elem elem;
+  typedef typename L::S S;
+  __shared__ __attribute__((aligned(16))) uint8_t bt_lds[256 * 128];
+  const int per_group = c.slabs * a.n_proj;
+  const int n_seg = *a.n_seg;
+  const int n_groups = a.group_start[n_seg];
+  const int q_total = (n_groups + 7) / 8 * per_group;
+  const int xcd = blockIdx.x & 7;
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int n = lane & 15, kg = lane >> 4, kq = kg & 1, lo_half = kg >> 1, m = lane & 15;
+  const uint16_t* __restrict__ pool = reinterpret_cast<const uint16_t*>(a.pool);
+  auto col_hash = [](int col) { return (col & 3) | (((col >> 4) & 1) << 2); };
+  for (int q = blockIdx.x >> 3; q < q_total; q += gridDim.x >> 3) {
+    const int group = (q / per_group) * 8 + xcd, slab = (q % per_group) / a.n_proj, p = (q % per_group) % a.n_proj;
+    if (group >= n_groups) continue;
+    const flp_lora_proj& pr = a.proj[p];
+    const int slab_begin = slab * 256;
+    if (slab_begin >= pr.d_out) continue;
+    const int s = find_segment(a.group_start, n_seg, group);
+    const int ad = a.seg_adapter[s];
+    const int r = a.rank[ad] < 16 * NT ? a.rank[ad] : 16 * NT;
+    if (r <= 0) continue;
+    const float sc = a.scale[ad];
+    const int RP = 16 * NT, TM = 16 * c.mt;
+    const int off0 = (group - a.group_start[s]) * c.group_tokens;
+    const int pos0 = a.seg_start[s] + off0;
+    const int pos_end = a.seg_start[s + 1];
+    const int pos_stop = pos0 + c.group_tokens < pos_end ? pos0 + c.group_tokens : pos_end;
+    const int64_t vrow0 = (int64_t)a.tile_start[s] * TM + off0;
+    const int rpb = (int)(a.block_elems / pr.d_out);
+
+    // ---- stage the slab's B coefficients: thread -> (rank, 8 consecutive columns), 16-byte loads along the
+    //      page rows, 2-byte stores into the transposed tile; ranks past r and columns past d_out hold zeros
+    __syncthreads();                                   // the previous item's fragments are no longer read
+    for (int it = tid; it < RP * 32; it += 256) {
+      const int rho = it >> 5, c8 = (it & 31) * 8;     // 32 column octets per rank
+      u32x4 raw = {0u, 0u, 0u, 0u};
+      if (rho < r && slab_begin + c8 < pr.d_out) {
+        const int i = pr.b_row_base[ad] + rho;
+        raw = *reinterpret_cast<const u32x4*>(pool + (int64_t)a.tables[pr.b_tab_off[ad] + i / rpb] * a.block_elems +
+                                              (int64_t)(i % rpb) * pr.d_out + slab_begin + c8);
+      }
+      uint16_t e8[8];
+      __builtin_memcpy(e8, &raw, 16);
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        const int col = c8 + j;
+        *reinterpret_cast<uint16_t*>(bt_lds + col * 128 + (((rho >> 3) ^ col_hash(col)) << 4) + (rho & 7) * 2) = e8[j];
+      }
+    }
+    __syncthreads();
+
+    for (int pos_t = pos0 + 16 * wave; pos_t < pos_stop; pos_t += 64) {
+      const int pos = pos_t + n;
+      const bool tvalid = pos < pos_stop;
+      const int tok = a.perm[tvalid ? pos : pos_stop - 1];
+      uint16_t* yrow = reinterpret_cast<uint16_t*>(pr.y) + (int64_t)tok * pr.ld_y + slab_begin + 16 * kg;
+      const float* brow = a.base32[p] ? a.base32[p] + (int64_t)tok * pr.d_out + slab_begin + 16 * kg : nullptr;
+      // ---- B operand: this token's scaled v for all rank tiles, high part in k-slots 0..15, remainder in 16..31
+      vec vb[NT];
+#pragma unroll
+      for (int nt = 0; nt < NT; ++nt) {
+        float v8[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) v8[j] = 0.f;
+        if (16 * nt < r) {
+          for (int ks = 0; ks < c.k_splits; ++ks) {
+            const float* vp =
+                a.v + (((int64_t)ks * c.v_rows + vrow0 + (pos - pos0)) * a.n_proj + p) * RP + 16 * nt + 8 * kq;
+            const f32x4 x0 = *reinterpret_cast<const f32x4*>(vp), x1 = *reinterpret_cast<const f32x4*>(vp + 4);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+              v8[j] += x0[j];
+              v8[4 + j] += x1[j];
+            }
+          }
+        }
+        vec out;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+          elem hi, lo;
+          L::split(v8[j] * sc, &hi, &lo);
+          out[j] = lo_half ? lo : hi;
+        }
+        vb[nt] = out;
+      }
+#pragma unroll
+      for (int ch = 0; ch < 4; ++ch) {
+        if (slab_begin + 64 * ch >= pr.d_out) continue;
+        u32x4 yraw[2];
+        if (!brow) {
+          yraw[0] = *reinterpret_cast<const u32x4*>(yrow + 64 * ch);
+          yraw[1] = *reinterpret_cast<const u32x4*>(yrow + 64 * ch + 8);
+        }
+        f32x4 acc[4];
+#pragma unroll
+        for (int tau = 0; tau < 4; ++tau) {
+          acc[tau] = f32x4{0.f, 0.f, 0.f, 0.f};
+          // row m of column tile tau is column 16*(m/4) + 4*tau + m%4 of the chunk: a lane's 16 results are 16
+          // consecutive columns and the four lanes of a token row cover one 128-byte line of y
+          const int col = 64 * ch + 16 * (m >> 2) + 4 * tau + (m & 3);
+          const uint8_t* frow = bt_lds + col * 128;
+          const int hsh = col_hash(col);
+#pragma unroll
+          for (int nt = 0; nt < NT; ++nt)
+            if (16 * nt < r)
+              acc[tau] = L::mfma(*reinterpret_cast<const vec*>(frow + (((2 * nt + kq) ^ hsh) << 4)), vb[nt], acc[tau]);
+        }
+        if (tvalid) {
+          uint16_t ys[16];
+          if (brow) {                            // unrounded base from the dense projection
+#pragma unroll
+            for (int tau = 0; tau < 4; ++tau) {
+              const f32x4 b4 = *reinterpret_cast<const f32x4*>(brow + 64 * ch + 4 * tau);
+#pragma unroll
+              for (int i = 0; i < 4; ++i) ys[4 * tau + i] = S::from_float(b4[i] + acc[tau][i]);
+            }
+          } else {
+            __builtin_memcpy(ys, &yraw[0], 32);
+#pragma unroll
+            for (int tau = 0; tau < 4; ++tau)
+#pragma unroll
+              for (int i = 0; i < 4; ++i) ys[4 * tau + i] = S::from_float(S::to_float(ys[4 * tau + i]) + acc[tau][i]);
+          }
+          u32x4 raw2[2];
+          __builtin_memcpy(raw2, ys, 32);
+          *reinterpret_cast<u32x4*>(yrow + 64 * ch) = raw2[0];
+          *reinterpret_cast<u32x4*>(yrow + 64 * ch + 8) = raw2[1];
+        }
+      }
+    }
+  }
+}
+
 template <typename L, int MT, int NT>
 flp_status launch_pair(const FlpLoraArgs& a, const FlpLoraMfma& c, hipStream_t stream) {
-  const size_t smem = (size_t)4 * MT * a.n_proj * NT * 4 * 64 * sizeof(float);
+  constexpr bool ONEP = NT >= 2;                       // one projection per workgroup from rank 17 on
+  const int n_pl = ONEP ? 1 : a.n_proj;
+  const size_t smem = (size_t)4 * MT * n_pl * NT * 4 * 64 * sizeof(float);
   static bool attr_set = false;
   if (!attr_set) {
-    FLP_TRY_HIP(hipFuncSetAttribute((const void*)lora_shrink_mfma_kernel<L, MT, NT>,
+    FLP_TRY_HIP(hipFuncSetAttribute((const void*)lora_shrink_mfma_kernel<L, MT, NT, ONEP>,
                                     hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));
     attr_set = true;
   }
-  hipLaunchKernelGGL((lora_shrink_mfma_kernel<L, MT, NT>), dim3((unsigned)(c.tiles_grid * c.k_splits)),
-                     dim3(256), smem, stream, a, c);
+  hipLaunchKernelGGL((lora_shrink_mfma_kernel<L, MT, NT, ONEP>),
+                     dim3((unsigned)(c.tiles_grid * c.k_splits * (ONEP ? a.n_proj : 1))), dim3(256), smem, stream, a, c);
   FLP_TRY_HIP(hipGetLastError());
   int max_dout = 0;
   for (int p = 0; p < a.n_proj; ++p) max_dout = a.proj[p].d_out > max_dout ? a.proj[p].d_out : max_dout;
@@ -366,7 +526,10 @@ flp_status launch_pair(const FlpLoraArgs& a, const FlpLoraMfma& c, hipStream_t s
     flp_set_error("LoRA (matrix-core path): %lld workgroups, too many for one launch", (long long)n_wg);
     return FLP_ENOTSUP;
   }
-  hipLaunchKernelGGL((lora_expand_mfma_kernel<L, NT>), dim3((unsigned)n_wg), dim3(64), 0, stream, a, ce);
+  if (NT >= 2 && c.cols_per_slab == 256)
+    hipLaunchKernelGGL((lora_expand_lds_kernel<L, NT>), dim3((unsigned)n_wg), dim3(256), 0, stream, a, ce);
+  else
+    hipLaunchKernelGGL((lora_expand_mfma_kernel<L, NT>), dim3((unsigned)n_wg), dim3(64), 0, stream, a, ce);
   FLP_TRY_HIP(hipGetLastError());
   return FLP_OK;
 }
