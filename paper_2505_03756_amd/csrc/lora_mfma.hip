@@ -186,6 +186,134 @@ __global__ __launch_bounds__(256) void lora_shrink_mfma_kernel(FlpLoraArgs a, Fl
   }
 }
 
+// ------------------------------------------------------------------------------- shrink, ranks above 16
+// The kernel above reads its operands straight from global memory in MFMA layout: 64-byte pieces of 16 rows
+// per instruction.  With 2 or 4 rank tiles per token tile that is mostly A traffic from L2 in 64-byte
+// requests, and the kernel runs far below the rate of the x stream.  Here a workgroup of four waves owns one
+// (32-token tile, projection, k split) and walks its k range in chunks of 64 coefficients: the chunk's x
+// rows (32 x 128 bytes) and A rows (16 NT x 128 bytes) travel as whole 128-byte lines into a ring of four LDS
+// stages with direct global-to-LDS loads (inline assembly, own s_waitcnt vmcnt; three chunks ahead), slots
+// XOR-swizzled by the row on the global side, and the waves split the (token tile, rank tile) pairs, so
+// no reduction across waves is needed.  Ranks past the adapter's rank read the adapter's first row: their v
+// entries are finite and meet zero coefficients in the expand kernel.
+typedef __attribute__((address_space(3))) uint8_t l_lds_u8;
+__device__ __forceinline__ void lload_lds16(uint64_t addr, uint32_t lds) {
+  asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(addr), "s"(lds) : "memory");
+}
+constexpr int lvmcnt(int n) { return (n & 15) | ((n >> 4) << 14) | (7 << 4) | (15 << 8); }   // s_waitcnt vmcnt(n) only
+
+template <typename L, int NT>
+__global__ __launch_bounds__(256) void lora_shrink_lds_kernel(FlpLoraArgs a, FlpLoraMfma c) {
+  typedef typename L::vec vec;
+  constexpr int kS = 4;                                // ring stages
+  constexpr int kStageB = 4096 + 2048 * NT;            // x rows, then A rows, 128 bytes each
+  constexpr int NINS = 4 + 2 * NT;                     // 1 KiB load instructions per chunk (8 rows each)
+  constexpr int NPER = NINS / 4;                       // of which each wave issues this many
+  constexpr int NP = 2 * NT / 4;                       // (token tile, rank tile) pairs per wave
+  __shared__ __attribute__((aligned(1024))) uint8_t smem[kS * kStageB];
+  const int n_seg = *a.n_seg;
+  const int n_tiles = a.tile_start[n_seg];
+  const int per_xcd = (n_tiles + 7) / 8;
+  const int per_tile = c.k_splits * a.n_proj;
+  const int ks = ((blockIdx.x >> 3) % per_tile) / a.n_proj, p = ((blockIdx.x >> 3) % per_tile) % a.n_proj;
+  const int tid = threadIdx.x, lane = tid & 63, row16 = lane & 15, kg = lane >> 4;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const uint16_t* __restrict__ pool = reinterpret_cast<const uint16_t*>(a.pool);
+  const flp_lora_proj& pr = a.proj[p];
+  const int rpb = (int)(a.block_elems / a.d_in);
+  const uint32_t lds0 = (uint32_t)(uintptr_t)(l_lds_u8*)smem;
+  for (int lt = (blockIdx.x >> 3) / per_tile; lt < per_xcd; lt += (gridDim.x >> 3) / per_tile) {
+    const int tile = (blockIdx.x & 7) * per_xcd + lt;
+    if (tile >= n_tiles) break;
+    const int s = find_segment(a.tile_start, n_seg, tile);
+    const int ad = a.seg_adapter[s];
+    const int r = a.rank[ad] < 16 * NT ? a.rank[ad] : 16 * NT;
+    const int pos0 = a.seg_start[s] + (tile - a.tile_start[s]) * 32;
+    const int pos_end = a.seg_start[s + 1];
+    const int kbeg = ks * c.k_per_split;
+    const int kend = kbeg + c.k_per_split < a.d_in ? kbeg + c.k_per_split : a.d_in;
+    const int n_chunks = r > 0 ? (kend - kbeg) / 64 : 0;
+
+    // ---- this lane's rows of the load instructions it issues: instruction j = wave + 4 i covers rows
+    //      8 j .. 8 j + 7 of the x tile (j < 4) or rows 8 (j - 4) .. of the A tile; lane l holds row l / 8,
+    //      LDS slot l % 8, i.e. the row's logical 16-byte piece (l % 8) ^ (row % 8)
+    uint64_t gaddr[NPER];
+    uint32_t ldst[NPER];
+#pragma unroll
+    for (int i = 0; i < NPER; ++i) {
+      const int j = wave + 4 * i, rl = lane >> 3;
+      const uint16_t* rowp;
+      int rowi;
+      if (j < 4) {
+        rowi = 8 * j + rl;
+        int pos = pos0 + rowi;
+        pos = pos < pos_end ? pos : pos_end - 1;       // padding rows repeat the last token
+        rowp = reinterpret_cast<const uint16_t*>(a.x) + (int64_t)a.perm[pos] * a.ld_x;
+        ldst[i] = 1024u * j;
+      } else {
+        rowi = 8 * (j - 4) + rl;
+        rowp = pool;
+        if (r > 0) {
+          const int ii = pr.a_row_base[ad] + (rowi < r ? rowi : 0);
+          rowp = pool + (int64_t)a.tables[pr.a_tab_off[ad] + ii / rpb] * a.block_elems + (int64_t)(ii % rpb) * a.d_in;
+        }
+        ldst[i] = 4096u + 1024u * (j - 4);
+      }
+      gaddr[i] = (uint64_t)(uintptr_t)(rowp + kbeg + 8 * ((lane & 7) ^ (rowi & 7)));
+    }
+    auto issue_chunk = [&](int t) {
+      const int tc = t < n_chunks ? t : n_chunks - 1;   // past the end: the last chunk again, into a free stage
+      const uint32_t dst = lds0 + (uint32_t)(t & (kS - 1)) * kStageB;
+#pragma unroll
+      for (int i = 0; i < NPER; ++i) lload_lds16(gaddr[i] + (uint64_t)tc * 128, dst + ldst[i]);
+    };
+
+    f32x4 acc[NP];
+    int offx[NP], offa[NP];
+#pragma unroll
+    for (int i = 0; i < NP; ++i) {
+      acc[i] = f32x4{0.f, 0.f, 0.f, 0.f};
+      const int pi = wave + 4 * i, mt = pi / NT, nt = pi % NT;
+      const int xr = 16 * mt + row16, ar = 16 * nt + row16;
+      offx[i] = xr * 128 + ((kg ^ (xr & 7)) << 4);                 // k step 0; step 1 is slot + 4: offset ^ 64
+      offa[i] = 4096 + ar * 128 + ((kg ^ (ar & 7)) << 4);
+    }
+
+    __builtin_amdgcn_s_waitcnt(lvmcnt(0));             // the loads above are in: only chunk loads are in flight below
+    __syncthreads();                                   // the previous item's stages are no longer read
+    if (n_chunks > 0) {
+#pragma unroll
+      for (int t = 0; t < kS - 1; ++t) issue_chunk(t);
+    }
+    for (int kt = 0; kt < n_chunks; ++kt) {
+      __builtin_amdgcn_s_waitcnt(lvmcnt(2 * NPER));    // chunk kt has landed (kt + 1 and kt + 2 may be in flight)
+      __syncthreads();
+      issue_chunk(kt + kS - 1);
+      const uint8_t* buf = smem + (kt & (kS - 1)) * kStageB;
+#pragma unroll
+      for (int k2 = 0; k2 < 2; ++k2)
+#pragma unroll
+        for (int i = 0; i < NP; ++i) {
+          const vec xf = *reinterpret_cast<const vec*>(buf + (offx[i] ^ (k2 << 6)));
+          const vec af = *reinterpret_cast<const vec*>(buf + (offa[i] ^ (k2 << 6)));
+          acc[i] = L::mfma(xf, af, acc[i]);
+        }
+    }
+    __builtin_amdgcn_s_waitcnt(lvmcnt(0));             // look-ahead loads past the last chunk must land before the ring is reused
+
+    // lane (rank column n = lane % 16, token rows 4 kg .. 4 kg + 3) of each pair
+    const int RP = 16 * NT;
+    float* __restrict__ vout = a.v + ((int64_t)ks * c.v_rows + (int64_t)tile * 32) * a.n_proj * RP;
+#pragma unroll
+    for (int i = 0; i < NP; ++i) {
+      const int pi = wave + 4 * i, mt = pi / NT, nt = pi % NT;
+#pragma unroll
+      for (int e = 0; e < 4; ++e)
+        vout[((int64_t)(16 * mt + 4 * kg + e) * a.n_proj + p) * RP + 16 * nt + row16] = acc[i][e];
+    }
+  }
+}
+
 // ------------------------------------------------------------------------------- expand
 // One wave per (tile group, column slab, projection).  The slab's B coefficients are gathered
 // once into MFMA A-operand fragments that stay in registers (64 VGPRs) while the wave walks
@@ -514,8 +642,17 @@ flp_status launch_pair(const FlpLoraArgs& a, const FlpLoraMfma& c, hipStream_t s
                                     hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));
     attr_set = true;
   }
-  hipLaunchKernelGGL((lora_shrink_mfma_kernel<L, MT, NT, ONEP>),
-                     dim3((unsigned)(c.tiles_grid * c.k_splits * (ONEP ? a.n_proj : 1))), dim3(256), smem, stream, a, c);
+  bool staged = false;
+  if constexpr (NT >= 2 && MT == 2) {
+    if (a.d_in % 64 == 0) {
+      hipLaunchKernelGGL((lora_shrink_lds_kernel<L, NT>), dim3((unsigned)(c.tiles_grid * c.k_splits * a.n_proj)),
+                         dim3(256), 0, stream, a, c);
+      staged = true;
+    }
+  }
+  if (!staged)
+    hipLaunchKernelGGL((lora_shrink_mfma_kernel<L, MT, NT, ONEP>),
+                       dim3((unsigned)(c.tiles_grid * c.k_splits * (ONEP ? a.n_proj : 1))), dim3(256), smem, stream, a, c);
   FLP_TRY_HIP(hipGetLastError());
   int max_dout = 0;
   for (int p = 0; p < a.n_proj; ++p) max_dout = a.proj[p].d_out > max_dout ? a.proj[p].d_out : max_dout;
