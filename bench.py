@@ -30,7 +30,7 @@ HBM_PEAK_GBS = 8000.0        # MI355X HBM3E, published
 # file (profiles/bench_7b_prefill_pmc.md), scaled by what the same counters read for a plain
 # device-to-device copy of 1 GiB (FETCH_SIZE reads half the bytes, WRITE_SIZE all of them).  Only
 # valid for the default workload and seed; null otherwise.
-MEASURED_TRAFFIC = {("7b_prefill", 20250504): 1.665e9, ("7b_decode", 20250505): 1.0151e10}
+MEASURED_TRAFFIC = {("7b_prefill", 20250504): 1.682e9, ("7b_decode", 20250505): 1.0151e10}
 MFMA_PEAK_TFLOPS = 2500.0    # dense fp16 / bf16 MFMA, published
 PCIE_PEAK_GBS = 64.0         # PCIe Gen5 x16, one direction
 
