@@ -334,11 +334,16 @@ extern "C" flp_status flp_lora_apply_paged(flp_pool* p, const flp_lora_batch* b,
         base_bytes[q] = (T * b->proj[q].d_out * 4 + 255) & ~(size_t)255;
         base_total += base_bytes[q];
       }
+  size_t splitk_bytes = 0;                     // slices of the dense product of a small batch
+  for (int q = 0; q < b->n_proj; ++q)
+    if (b->proj[q].w_base && p->elem_bytes == 2)
+      splitk_bytes = std::max(splitk_bytes, flp_gemm_splitk_bytes(b->n_tokens, b->proj[q].d_out));
+  splitk_bytes = (splitk_bytes + 255) & ~(size_t)255;
   const size_t v_bytes = (v_elems * 4 + 255) & ~(size_t)255;
   const size_t seg_bytes = ((size_t)(4 * b->n_adapters + 5) * 4 + 255) & ~(size_t)255;
   const size_t perm_bytes = (T * 4 + 255) & ~(size_t)255;
   void* ws = nullptr;
-  FLP_TRY(flp_workspace(p, v_bytes + seg_bytes + perm_bytes + wt_bytes + base_total, &ws));
+  FLP_TRY(flp_workspace(p, v_bytes + seg_bytes + perm_bytes + wt_bytes + base_total + splitk_bytes, &ws));
   FlpLoraArgs a{};
   a.pool = p->dev_base;
   a.block_elems = p->block_elems;
@@ -368,12 +373,13 @@ extern "C" flp_status flp_lora_apply_paged(flp_pool* p, const flp_lora_batch* b,
   {
     uint8_t* wt = w + v_bytes + seg_bytes + perm_bytes;
     uint8_t* basep = wt + wt_bytes;
+    float* splitk = splitk_bytes ? (float*)(basep + base_total) : nullptr;
     for (int q = 0; q < b->n_proj; ++q) {
       if (!b->proj[q].w_base) continue;
       float* y32 = p->elem_bytes == 2 ? (float*)basep : nullptr;
       FLP_TRY(flp_launch_base_gemm(p->cfg.dtype, b->x, b->ld_x, b->proj[q].w_base, b->proj[q].w_base_layout,
                                    b->proj[q].y, b->proj[q].ld_y, b->n_tokens, b->proj[q].d_out, b->d_in, wt, y32,
-                                   stream));
+                                   splitk, splitk_bytes, stream));
       a.base32[q] = y32;
       basep += base_bytes[q];
     }

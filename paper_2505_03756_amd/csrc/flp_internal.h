@@ -163,4 +163,7 @@ flp_status flp_launch_lora_segment(int32_t T, const int32_t* token_adapter, int3
 flp_status flp_launch_lora_mfma(int dtype, const FlpLoraArgs& a, const FlpLoraMfma& c, hipStream_t stream);
 flp_status flp_launch_lora_simple(int dtype, const FlpLoraArgs& a, hipStream_t stream);
 flp_status flp_launch_base_gemm(int dtype, const void* x, int64_t ld_x, const void* w, int w_layout, void* y,
-                                int64_t ld_y, int M, int N, int K, void* wt_scratch, float* y32, hipStream_t stream);
+                                int64_t ld_y, int M, int N, int K, void* wt_scratch, float* y32, float* splitk_scratch,
+                                size_t splitk_bytes, hipStream_t stream);
+// bytes of split-K scratch worth offering for an [M, N] product (0 for large batches, which are not split)
+inline size_t flp_gemm_splitk_bytes(int M, int N) { return M <= 1024 ? (size_t)8 * M * N * 4 : 0; }

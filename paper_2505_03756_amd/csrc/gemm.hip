@@ -64,10 +64,14 @@ __device__ __forceinline__ int tile_off(int r, int c) { return (r >> 1) * 256 + 
 // The product is stored rounded into y and, when y32 is given, also unrounded as fp32 ([M, N]
 // dense): the LoRA expand kernel adds the adapter's delta to the unrounded value and rounds once;
 // rows of tokens without an adapter keep the rounded value.
+// With gridDim.z > 1 the contraction is split: slice z covers K / gridDim.z coefficients and writes its
+// unrounded partial product to part + z * M * N (dense fp32); gemm_splitk_reduce_kernel adds the slices in
+// order and rounds.  Small batches (decode) have too few 128 x 128 tiles to occupy the chip otherwise.
 template <typename G>
 __global__ __launch_bounds__(256, 2) void gemm_nt_kernel(const uint16_t* __restrict__ x, int64_t ld_x,
                                                          const uint16_t* __restrict__ wt, uint16_t* __restrict__ y,
-                                                         int64_t ld_y, float* __restrict__ y32, int M, int N, int K) {
+                                                         int64_t ld_y, float* __restrict__ y32, int M, int N, int K,
+                                                         float* __restrict__ part) {
   typedef typename G::vec vec;
   __shared__ __attribute__((aligned(16))) uint8_t smem[2][2 * kTile];      // [buffer][Wt tile | x tile]
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, lr = lane & 31, hf = lane >> 5;
@@ -107,13 +111,17 @@ __global__ __launch_bounds__(256, 2) void gemm_nt_kernel(const uint16_t* __restr
   // A-operand row a of a 32-row tile is output column 16*((a>>2)&1) + 4*(a>>3) + (a&3) of that tile
   const int acol = (((lr >> 2) & 1) << 4) | ((lr >> 3) << 2) | (lr & 3);
 
-  const int nk = K / BK;
-  load_tiles(0);
+  const int nk = K / BK / (int)gridDim.z, kt0 = (int)blockIdx.z * nk;    // this slice's k tiles
+  if (gridDim.z > 1) {
+    y = nullptr;
+    y32 = part + (int64_t)blockIdx.z * M * N;
+  }
+  load_tiles(kt0 * BK);
   store_tiles(smem[0]);
   __syncthreads();
   for (int kt = 0; kt < nk; ++kt) {
     const uint8_t* buf = smem[kt & 1];
-    if (kt + 1 < nk) load_tiles((kt + 1) * BK);
+    if (kt + 1 < nk) load_tiles((kt0 + kt + 1) * BK);
 #pragma unroll
     for (int kk = 0; kk < BK / 16; ++kk) {
       vec af[2], bf[2];
@@ -146,6 +154,7 @@ __global__ __launch_bounds__(256, 2) void gemm_nt_kernel(const uint16_t* __restr
         for (int e = 0; e < 16; ++e)
           if (n + e < N) yp32[e] = acc[i][j][e];
       }
+      if (!y) continue;                              // a slice of a split contraction writes only its partial
       uint16_t o[16];
 #pragma unroll
       for (int e = 0; e < 16; ++e) o[e] = G::out(acc[i][j][e]);
@@ -351,6 +360,21 @@ __global__ __launch_bounds__(256, 1) void gemm_nt256_kernel(const uint16_t* __re
   }
 }
 
+// y[m, n] = round(sum over the slices, in slice order); y32 (optional) gets the unrounded sum
+template <typename G>
+__global__ __launch_bounds__(256) void gemm_splitk_reduce_kernel(const float* __restrict__ part, int slices, int M, int N,
+                                                                 uint16_t* __restrict__ y, int64_t ld_y,
+                                                                 float* __restrict__ y32) {
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x, total = (int64_t)M * N;
+  if (i >= total) return;
+  float sum = part[i];
+  for (int z = 1; z < slices; ++z) sum += part[(int64_t)z * total + i];
+  const int64_t m = i / N;
+  const int n = (int)(i - m * N);
+  y[m * ld_y + n] = G::out(sum);
+  if (y32) y32[i] = sum;
+}
+
 __global__ __launch_bounds__(256) void gemm_f32_kernel(const float* __restrict__ x, int64_t ld_x,
                                                        const float* __restrict__ w, int64_t w_k_stride,
                                                        int64_t w_n_stride, float* __restrict__ y, int64_t ld_y, int M,
@@ -368,7 +392,8 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(const float* __restrict__
 // types with layout 0 only) must hold N*K elements; `y32` (16-bit types, optional) receives the
 // unrounded product as dense fp32 [M, N].
 flp_status flp_launch_base_gemm(int dtype, const void* x, int64_t ld_x, const void* w, int w_layout, void* y,
-                                int64_t ld_y, int M, int N, int K, void* wt_scratch, float* y32, hipStream_t stream) {
+                                int64_t ld_y, int M, int N, int K, void* wt_scratch, float* y32, float* splitk_scratch,
+                                size_t splitk_bytes, hipStream_t stream) {
   if (M <= 0 || N <= 0 || K <= 0) return FLP_OK;
   if (dtype == FLP_F32) {
     hipLaunchKernelGGL(gemm_f32_kernel, dim3((N + 255) / 256, M), dim3(256), 0, stream, (const float*)x, ld_x,
@@ -403,12 +428,29 @@ flp_status flp_launch_base_gemm(int dtype, const void* x, int64_t ld_x, const vo
     FLP_TRY_HIP(hipGetLastError());
     return FLP_OK;
   }
-  dim3 grid((N + BN - 1) / BN, (M + BM - 1) / BM);
+  // few tiles (decode batches): split the contraction over up to 8 slices until about 256 workgroups run
+  const int tiles = ((N + BN - 1) / BN) * ((M + BM - 1) / BM);
+  int slices = 1;
+  while (slices < 8 && tiles * slices < 192 && (K / BK) % (slices * 2) == 0 && K / (slices * 2) >= 512 &&
+         splitk_scratch && (size_t)slices * 2 * M * N * 4 <= splitk_bytes)
+    slices *= 2;
+  dim3 grid((N + BN - 1) / BN, (M + BM - 1) / BM, slices);
   if (dtype == FLP_F16)
-    hipLaunchKernelGGL(gemm_nt_kernel<GF16>, grid, dim3(256), 0, stream, xs, ld_x, ws, (uint16_t*)y, ld_y, y32, M, N, K);
+    hipLaunchKernelGGL(gemm_nt_kernel<GF16>, grid, dim3(256), 0, stream, xs, ld_x, ws, (uint16_t*)y, ld_y, y32, M, N, K,
+                       splitk_scratch);
   else
     hipLaunchKernelGGL(gemm_nt_kernel<GBF16>, grid, dim3(256), 0, stream, xs, ld_x, ws, (uint16_t*)y, ld_y, y32, M, N,
-                       K);
+                       K, splitk_scratch);
   FLP_TRY_HIP(hipGetLastError());
+  if (slices > 1) {
+    const unsigned nb = (unsigned)(((int64_t)M * N + 255) / 256);
+    if (dtype == FLP_F16)
+      hipLaunchKernelGGL(gemm_splitk_reduce_kernel<GF16>, dim3(nb), dim3(256), 0, stream, splitk_scratch, slices, M, N,
+                         (uint16_t*)y, ld_y, y32);
+    else
+      hipLaunchKernelGGL(gemm_splitk_reduce_kernel<GBF16>, dim3(nb), dim3(256), 0, stream, splitk_scratch, slices, M, N,
+                         (uint16_t*)y, ld_y, y32);
+    FLP_TRY_HIP(hipGetLastError());
+  }
   return FLP_OK;
 }

@@ -7,6 +7,7 @@
 
 #include <algorithm>
 #include <cmath>
+#include <mutex>
 
 #include "fllayer.h"
 #include "flp_internal.h"
@@ -328,8 +329,16 @@ extern "C" flp_status fll_layer_forward(flp_pool* p, const fll_layer_config* c, 
           flp_set_error("fll_layer_forward: projection %d: d_in %d is not a multiple of 64", which[i], d_in);
           return FLP_ENOTSUP;
         }
+        // split-K slices of a small batch live in the pool's workspace (stream order keeps them apart from the
+        // LoRA intermediates of the calls before and after)
+        const size_t sk_bytes = p->elem_bytes == 2 ? flp_gemm_splitk_bytes(T, d_outs[i]) : 0;
+        void* sk = nullptr;
+        if (sk_bytes) {
+          std::lock_guard<std::mutex> lk(p->mu);
+          FLP_TRY(flp_workspace(p, sk_bytes, &sk));
+        }
         FLP_TRY(flp_launch_base_gemm(dtype, x, d_in, ws[i], 1, ys[i], d_outs[i], T, d_outs[i], d_in, nullptr, nullptr,
-                                     (hipStream_t)hip_stream));
+                                     (float*)sk, sk_bytes, (hipStream_t)hip_stream));
         continue;
       }
       if (n_set != 4) {
