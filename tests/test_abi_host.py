@@ -208,3 +208,12 @@ def test_pool_create_rejects_bad_geometry():
     with pytest.raises(flpool.FlpError) as e:
         flpool.Pool("f16", 2, 64, 4, 0, dev=0x1010)       # not 256-byte aligned
     assert e.value.code == flpool.FLP_EINVAL
+
+
+def test_bench_refuses_more_than_one_gpu():
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True,
+                       timeout=120)
+    assert r.returncode == 2
+    assert "ONE GPU" in r.stderr and r.stdout.strip() == ""
