@@ -279,3 +279,26 @@ def test_round_to_dtype_matches_numpy_formats():
     v32 = v.astype(np.float32).astype(np.float64)
     ok = v32 == v                                    # quantize() rounds from fp32; compare where that is exact
     assert np.array_equal(got[ok], want[ok])
+
+
+def test_block_size_is_a_storage_detail():
+    """The same keys and values stored in blocks of 16 and of 32 positions (other slot strides, other tables)
+    give the same attention, and each block size places element (head, slot, channel) where the layout rule
+    says (K at (g*bt + s)*d + c, V at n_kv*bt*d + (g*d + c)*bt + s)."""
+    rng = np.random.default_rng(33)
+    L, n_kv, d, n_h, P = 77, 2, 8, 4, 50
+    K = rng.standard_normal((L, n_kv, d))
+    V = rng.standard_normal((L, n_kv, d))
+    q = rng.standard_normal((L - P, n_h, d)).astype(np.float32)
+    outs = []
+    for bt in (16, 32):
+        pool, table, Kq, Vq = _paged_from_contig(rng, K, V, bt)
+        pos, g, c = 41, 1, 5
+        blk = pool[table[0, pos // bt]]
+        assert blk[(g * bt + pos % bt) * d + c] == np.float32(K[pos, g, c])
+        assert blk[n_kv * bt * d + (g * d + c) * bt + pos % bt] == np.float32(V[pos, g, c])
+        outs.append(oracle.paged_attention(pool, "f32", bt, n_kv, d, n_h, [0, L - P], [P], table, q))
+    assert np.array_equal(outs[0], outs[1])
+    assert np.allclose(outs[0], _sdpa_reference(K.astype(np.float32).astype(np.float64),
+                                                V.astype(np.float32).astype(np.float64), q.astype(np.float64), P, n_h),
+                       atol=1e-12)
