@@ -190,3 +190,49 @@ def test_layer_forward_matches_composed_oracle(name):
         m = np.isfinite(a) & np.isfinite(b)
         assert (np.isfinite(a) == np.isfinite(b)).all()
         assert np.abs(a[m] - b[m]).max() <= 4 * ULP[cfg.dtype] * max(1.0, np.abs(b[m]).max())
+
+
+def test_two_layer_stack_with_per_layer_pools():
+    """Two layers, each with its own pool (the same block ids and tables in both) and its own weights: the second
+    layer's input is the first one's residual stream; each layer appends its K/V to its own pool."""
+    import torch
+    from paper_2505_03756_amd import flpool
+    from paper_2505_03756_amd.harness import GpuPool
+    cfg = layer_cfg("f16", seed=46)
+    step = wl.make_step(cfg)
+    T = step.n_tokens
+    dev0 = resident_pool(step)
+    stub = np.zeros((1, cfg.block_elems), dev0.dtype)
+    g = GpuStep(step, dev0, stub)
+    gp1 = GpuPool(cfg, dev0, stub)                                     # layer 1's pool: same blocks at the same ids
+    W = [make_weights(cfg, np.random.default_rng(70 + l)) for l in range(2)]
+    h0_st, _ = lo.round_store(np.random.default_rng(9).normal(0, 1, (T, cfg.hidden)), cfg.dtype)
+    pos = np.concatenate([step.prefix_len[i] + np.arange(step.cu_new[i + 1] - step.cu_new[i])
+                          for i in range(cfg.n_seqs)]).astype(np.int32)
+    pools = [g.pool, gp1.pool]
+    layers = [fllayer.Layer(pools[l], cfg.hidden, cfg.n_q_heads, cfg.mlp_dim, {k: to_dev(v) for k, v in W[l].items()})
+              for l in range(2)]
+    batch = fllayer.Batch(step.cu_new, step.prefix_len, to_dev(pos), g.kv_tables, g.token_adapter, g.rank, g.scale,
+                          g.lora_tables, g.proj, n_adapters=len(step.rank), max_rank=int(step.rank.max()),
+                          max_blocks_per_seq=step.kv_tables.shape[1])
+    nbytes = layers[0].scratch_bytes(T)
+    scratch = torch.zeros(nbytes + 256, dtype=torch.uint8, device="cuda")
+    sp = (scratch.data_ptr() + 255) & ~255
+    h = to_dev(h0_st)
+    for ly in layers:
+        ly.forward(batch, h, sp, nbytes)
+    torch.cuda.synchronize()
+    got = lo.load(to_np(h, h0_st.dtype), cfg.dtype)
+    want_st, pools_o = h0_st, [dev0.copy(), dev0.copy()]
+    for l in range(2):
+        want_st, _ = lo.layer_forward(cfg, step, pools_o[l], W[l], want_st, pos)
+    want = lo.load(want_st, cfg.dtype)
+    ok, worst, nbad = close(got, want, 16 * ULP[cfg.dtype], 16 * ULP[cfg.dtype])     # two layers: twice one layer's bound
+    assert ok, "h: max err %g, %d of %d out of tolerance" % (worst, nbad, got.size)
+    # each pool holds its own layer's keys: the two layers appended different K rows to the same block ids
+    fresh = step.fresh_block_ids
+    img0, img1 = g.dev_image()[fresh], to_np(gp1.dev, dev0.dtype)[fresh]
+    assert not np.array_equal(img0, img1)
+    a, b = lo.load(img1, cfg.dtype), lo.load(pools_o[1][fresh], cfg.dtype)
+    m = np.isfinite(a) & np.isfinite(b)
+    assert (np.isfinite(a) == np.isfinite(b)).all() and np.abs(a[m] - b[m]).max() <= 16 * ULP[cfg.dtype] * max(1.0, np.abs(b[m]).max())
