@@ -314,6 +314,123 @@ __global__ __launch_bounds__(256) void lora_shrink_lds_kernel(FlpLoraArgs a, Flp
   }
 }
 
+// The same staging for ranks up to 16, where the projections of a call are fused: the A rows of all NPJ
+// projections (16 rank rows each) sit behind the 32 x rows of a chunk, x is fetched once for all of them,
+// and the waves split the (token tile, projection) pairs.  When the load instructions of a chunk do not
+// divide by four, a wave repeats one of its own loads, so that every wave has the same number in flight.
+template <typename L, int NPJ>
+__global__ __launch_bounds__(256) void lora_shrink_lds16_kernel(FlpLoraArgs a, FlpLoraMfma c) {
+  typedef typename L::vec vec;
+  constexpr int kS = 4;
+  constexpr int kStageB = 4096 + 2048 * NPJ;
+  constexpr int NINS = 4 + 2 * NPJ;
+  constexpr int NPER = (NINS + 3) / 4;
+  constexpr int NP = (2 * NPJ + 3) / 4;
+  __shared__ __attribute__((aligned(1024))) uint8_t smem[kS * kStageB];
+  const int n_seg = *a.n_seg;
+  const int n_tiles = a.tile_start[n_seg];
+  const int per_xcd = (n_tiles + 7) / 8;
+  const int ks = (blockIdx.x >> 3) % c.k_splits;
+  const int tid = threadIdx.x, lane = tid & 63, row16 = lane & 15, kg = lane >> 4;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const uint16_t* __restrict__ pool = reinterpret_cast<const uint16_t*>(a.pool);
+  const int rpb = (int)(a.block_elems / a.d_in);
+  const uint32_t lds0 = (uint32_t)(uintptr_t)(l_lds_u8*)smem;
+  for (int lt = (blockIdx.x >> 3) / c.k_splits; lt < per_xcd; lt += (gridDim.x >> 3) / c.k_splits) {
+    const int tile = (blockIdx.x & 7) * per_xcd + lt;
+    if (tile >= n_tiles) break;
+    const int s = find_segment(a.tile_start, n_seg, tile);
+    const int ad = a.seg_adapter[s];
+    const int r = a.rank[ad] < 16 ? a.rank[ad] : 16;
+    const int pos0 = a.seg_start[s] + (tile - a.tile_start[s]) * 32;
+    const int pos_end = a.seg_start[s + 1];
+    const int kbeg = ks * c.k_per_split;
+    const int kend = kbeg + c.k_per_split < a.d_in ? kbeg + c.k_per_split : a.d_in;
+    const int n_chunks = r > 0 ? (kend - kbeg) / 64 : 0;
+
+    uint64_t gaddr[NPER];
+    uint32_t ldst[NPER];
+#pragma unroll
+    for (int i = 0; i < NPER; ++i) {
+      int j = wave + 4 * i;
+      if (j >= NINS) j -= 4;                           // no such instruction: this wave's previous one again
+      const int rl = lane >> 3;
+      const uint16_t* rowp;
+      int rowi;
+      if (j < 4) {
+        rowi = 8 * j + rl;
+        int pos = pos0 + rowi;
+        pos = pos < pos_end ? pos : pos_end - 1;       // padding rows repeat the last token
+        rowp = reinterpret_cast<const uint16_t*>(a.x) + (int64_t)a.perm[pos] * a.ld_x;
+        ldst[i] = 1024u * j;
+      } else {
+        const int pj = (j - 4) >> 1;                   // projection whose A rows this instruction moves
+        rowi = 8 * ((j - 4) & 1) + rl;                 // rank row
+        rowp = pool;
+        if (r > 0) {
+          const flp_lora_proj& pr = a.proj[pj];
+          const int ii = pr.a_row_base[ad] + (rowi < r ? rowi : 0);
+          rowp = pool + (int64_t)a.tables[pr.a_tab_off[ad] + ii / rpb] * a.block_elems + (int64_t)(ii % rpb) * a.d_in;
+        }
+        ldst[i] = 4096u + 1024u * (j - 4);
+      }
+      gaddr[i] = (uint64_t)(uintptr_t)(rowp + kbeg + 8 * ((lane & 7) ^ (rowi & 7)));
+    }
+    auto issue_chunk = [&](int t) {
+      const int tc = t < n_chunks ? t : n_chunks - 1;
+      const uint32_t dst = lds0 + (uint32_t)(t & (kS - 1)) * kStageB;
+#pragma unroll
+      for (int i = 0; i < NPER; ++i) lload_lds16(gaddr[i] + (uint64_t)tc * 128, dst + ldst[i]);
+    };
+
+    f32x4 acc[NP];
+    int offx[NP], offa[NP];
+#pragma unroll
+    for (int i = 0; i < NP; ++i) {
+      acc[i] = f32x4{0.f, 0.f, 0.f, 0.f};
+      int pi = wave + 4 * i;
+      pi = pi < 2 * NPJ ? pi : 0;                      // no such pair: pair 0 again, not stored
+      const int mt = pi / NPJ, pj = pi % NPJ;
+      const int xr = 16 * mt + row16, ar = 16 * pj + row16;
+      offx[i] = xr * 128 + ((kg ^ (xr & 7)) << 4);
+      offa[i] = 4096 + ar * 128 + ((kg ^ (ar & 7)) << 4);
+    }
+
+    __builtin_amdgcn_s_waitcnt(lvmcnt(0));
+    __syncthreads();
+    if (n_chunks > 0) {
+#pragma unroll
+      for (int t = 0; t < kS - 1; ++t) issue_chunk(t);
+    }
+    for (int kt = 0; kt < n_chunks; ++kt) {
+      __builtin_amdgcn_s_waitcnt(lvmcnt(2 * NPER));
+      __syncthreads();
+      issue_chunk(kt + kS - 1);
+      const uint8_t* buf = smem + (kt & (kS - 1)) * kStageB;
+#pragma unroll
+      for (int k2 = 0; k2 < 2; ++k2)
+#pragma unroll
+        for (int i = 0; i < NP; ++i) {
+          const vec xf = *reinterpret_cast<const vec*>(buf + (offx[i] ^ (k2 << 6)));
+          const vec af = *reinterpret_cast<const vec*>(buf + (offa[i] ^ (k2 << 6)));
+          acc[i] = L::mfma(xf, af, acc[i]);
+        }
+    }
+    __builtin_amdgcn_s_waitcnt(lvmcnt(0));
+
+    float* __restrict__ vout = a.v + ((int64_t)ks * c.v_rows + (int64_t)tile * 32) * a.n_proj * 16;
+#pragma unroll
+    for (int i = 0; i < NP; ++i) {
+      const int pi = wave + 4 * i;
+      if (pi < 2 * NPJ) {
+        const int mt = pi / NPJ, pj = pi % NPJ;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) vout[((int64_t)(16 * mt + 4 * kg + e) * a.n_proj + pj) * 16 + row16] = acc[i][e];
+      }
+    }
+  }
+}
+
 // ------------------------------------------------------------------------------- expand
 // One wave per (tile group, column slab, projection).  The slab's B coefficients are gathered
 // once into MFMA A-operand fragments that stay in registers (64 VGPRs) while the wave walks
@@ -647,6 +764,18 @@ flp_status launch_pair(const FlpLoraArgs& a, const FlpLoraMfma& c, hipStream_t s
     if (a.d_in % 64 == 0) {
       hipLaunchKernelGGL((lora_shrink_lds_kernel<L, NT>), dim3((unsigned)(c.tiles_grid * c.k_splits * a.n_proj)),
                          dim3(256), 0, stream, a, c);
+      staged = true;
+    }
+  }
+  if constexpr (NT == 1 && MT == 2) {
+    if (a.d_in % 64 == 0) {
+      const dim3 g16((unsigned)(c.tiles_grid * c.k_splits));
+      switch (a.n_proj) {
+        case 1: hipLaunchKernelGGL((lora_shrink_lds16_kernel<L, 1>), g16, dim3(256), 0, stream, a, c); break;
+        case 2: hipLaunchKernelGGL((lora_shrink_lds16_kernel<L, 2>), g16, dim3(256), 0, stream, a, c); break;
+        case 3: hipLaunchKernelGGL((lora_shrink_lds16_kernel<L, 3>), g16, dim3(256), 0, stream, a, c); break;
+        default: hipLaunchKernelGGL((lora_shrink_lds16_kernel<L, 4>), g16, dim3(256), 0, stream, a, c); break;
+      }
       staged = true;
     }
   }
