@@ -305,9 +305,12 @@ extern "C" flp_status flp_lora_apply_paged(flp_pool* p, const flp_lora_batch* b,
     const int32_t seg_bound = (int32_t)std::min<size_t>((size_t)b->n_adapters, T);
     c.tiles_bound = (int32_t)((T + tm - 1) / tm) + seg_bound;
     c.tiles_grid = (std::min(c.tiles_bound, (int32_t)((T + tm - 1) / tm) + 64) + 7) / 8 * 8;
-    // split K until about 2048 workgroups are in flight, in pieces of 128 coefficients
+    // split K until enough workgroups are in flight, in pieces of 128 coefficients: about 2048 for the kernel
+    // that reads its operands from global memory (it lives on loads in flight), about 1024 for the LDS-staged
+    // ones (they keep three chunks in flight themselves; fewer partial sums for the expand kernel to add)
+    const int wg_target = (c.mt == 2 && b->d_in % 64 == 0) ? 1024 : 2048;
     int ks = 1;
-    while (ks < 8 && c.tiles_grid * ks < 2048 && b->d_in / (ks * 2) >= 256) ks *= 2;
+    while (ks < 8 && c.tiles_grid * ks < wg_target && b->d_in / (ks * 2) >= 256) ks *= 2;
     c.k_splits = ks;
     c.k_per_split = ((b->d_in + ks - 1) / ks + 127) / 128 * 128;
     c.v_rows = c.tiles_bound * tm;
