@@ -195,6 +195,42 @@ def test_lora_matrix_core_shapes(name):
         assert err.max() <= ulp * (np.abs(want).max() + 1.0), (n, err.max())
 
 
+@pytest.mark.parametrize("dtype,T", [("bf16", 1), ("bf16", 63), ("f32", 257), ("bf16", 1023), ("f16", 1024),
+                                     ("f32", 1025)])
+def test_lora_small_batches_share_adapter_pages(dtype, T):
+    """The per-token kernels take the tokens of one adapter four at a time (batches of up to 1024 tokens): batches
+    around that limit and around the 64-token words of the kernels' bit mask, with adapters that own one token, a
+    few, or a third of the batch, tokens without an adapter, and widths that do not fill the column slabs."""
+    cfg = small_cfg(dtype, hidden=320, n_q_heads=5, n_kv_heads=1, head_dim=64, n_seqs=T, prefix_range=(0, 0),
+                    new_range=(1, 1), decode_frac=1.0, n_adapters=40, ranks=(8, 16, 32, 64), n_dev_blocks=2600,
+                    swap_in_frac=0.0, seed=300 + T)
+    step = wl.make_step(cfg)
+    rng = np.random.default_rng(T)
+    ta = step.token_adapter.copy()
+    if T > 8:
+        ta[rng.choice(T, size=T // 3, replace=False)] = 3               # one heavy adapter: many fours
+        ta[rng.choice(T, size=T // 10, replace=False)] = -1             # tokens without an adapter
+        ta[T - 1] = 3
+    step.token_adapter = ta
+    dev0 = resident_pool(step)
+    g = GpuStep(step, dev0, np.zeros((1, cfg.block_elems), dev0.dtype))
+    rtol, atol = TOL[cfg.dtype]
+    got = g.lora(["q", "k", "v"])
+    got.update(g.lora(["o"]))
+    for n in ("q", "k", "v", "o"):
+        pr = step.proj[n]
+        want = oracle.lora_apply(dev0, cfg.dtype, step.acts["x"], ta, step.rank, step.scale, pr.a_tab_off,
+                                 pr.a_row_base, pr.b_tab_off, pr.b_row_base, step.lora_tables, pr.d_out,
+                                 y_in=step.acts["base_" + n])
+        ok, worst, nbad = close(wl.dequantize(got[n], cfg.dtype), want, rtol, atol)
+        assert ok, "%s: max err %g, %d elements out of tolerance" % (n, worst, nbad)
+        base = wl.dequantize(step.acts["base_" + n], cfg.dtype)
+        none = ta < 0
+        if none.any():                                                   # rows without an adapter are untouched
+            assert np.array_equal(got[n][none], step.acts["base_" + n][none])
+        assert np.abs(want - base)[~none].max() > 0
+
+
 @pytest.mark.parametrize("name", ["tiny", "f16_prefill", "bf16_gqa_mixed", "f16_long_segments", "bf16_dense_tail"])
 def test_lora_with_dense_base(name):
     """w_base given: y = x.W_base + delta, the library computes the base term itself (Eq. 1's W)."""
