@@ -177,18 +177,19 @@ __global__ __launch_bounds__(256, 2) void gemm_nt_kernel(const uint16_t* __restr
 // Four waves, each a 128 x 128 corner (4 x 4 accumulators of mfma_f32_32x32x16: 256 accumulator registers,
 // one wave per SIMD), so that a k step of 16 costs 8 fragment reads for 16 MFMAs: LDS traffic per flop is
 // half that of a 64 x 64 corner, and the operand tiles are fetched from L2 half as often as with 128 x 128
-// workgroup tiles.  Operand tiles are 256 rows x 32 coefficients (16 KiB each) in a ring of four stages; tile
-// t + 3 is requested right after the barrier of tile t with global_load_lds_dwordx4 (no registers, no LDS
-// store instructions), written as inline assembly so that the compiler's own counter waits leave them alone;
-// the wave waits for all but the newest tile's loads before each barrier, so tiles t and t + 1 are complete
-// when tile t is multiplied and the fragments of the next step - also across the tile boundary - are read while
-// the current step's MFMAs run.  LDS layout: four 64-byte rows share a 256-byte line and the line's 16 slots
-// are XOR-ed with the line index, which makes the 16 lanes that read one 16-byte chunk of 16 consecutive rows
-// hit 16 different slots; the swizzle is applied on the global side (a lane fetches the chunk that belongs
-// at its fixed LDS slot).  Workgroups of one XCD (ids congruent modulo 8) cover 4 x 8 blocks of tiles, so
-// the 32 that run together fetch 12 operand panels instead of 64.
-constexpr int GT = 256, GK = 32, kGStage = 2 * GT * GK * 2, kGStages = 4;   // 32 KiB per stage
-constexpr int kGLoads = 8;                                                    // direct loads per wave and tile
+// workgroup tiles.  Operand tiles are 256 rows x 64 coefficients (32 KiB each, 64 KiB per stage, two stages):
+// a row's 64 coefficients are one whole 128-byte line, and a global_load_lds_dwordx4 instruction (no registers,
+// no LDS store instructions; inline assembly with its own s_waitcnt vmcnt) moves 8 whole lines.  Requests of
+// half a line (tiles of 32 coefficients in a ring of four) made every line cross from L2 twice and were 4-8 %
+// slower.  One barrier per stage, before its last k step: by then the wave has waited for its loads of the next
+// stage and has read the last fragments of this one, so after the barrier the next stage is complete for
+// everybody (its first fragments are read during the last step) and this stage's buffer is free for the stage
+// after next.  LDS layout: row r at r * 128, its 16-byte chunk c in slot c ^ gswz(r), which spreads the 16 lanes
+// that read one chunk of their (permuted) 16 rows over the 16 slots of a 256-byte bank window; the swizzle is
+// applied on the global side (a lane fetches the chunk that belongs at its fixed LDS slot).  Workgroups of one
+// XCD (ids congruent modulo 8) cover 4 x 8 blocks of tiles, so the 32 that run together fetch 12 operand panels
+// instead of 64.
+constexpr int GT = 256, GK = 64, kGOperand = GT * GK * 2, kGStage = 2 * kGOperand, kGStages = 2;   // 64 KiB per stage
 // s_waitcnt immediate (gfx9 encoding: vmcnt[3:0] + [15:14], expcnt[6:4], lgkmcnt[11:8]): vmcnt only
 constexpr int vmcnt_imm(int n) { return (n & 15) | ((n >> 4) << 14) | (7 << 4) | (15 << 8); }
 
@@ -198,11 +199,10 @@ __device__ __forceinline__ void gload_lds16(const void* base, uint32_t voff, uin
 }
 typedef __attribute__((address_space(3))) uint8_t g_lds_u8;
 
-// byte offset of 16-byte chunk c (0..3) of row r (0..255) inside a 256 x 32 operand tile
-__device__ __forceinline__ int gtile_off(int r, int c) {
-  const int line = r >> 2;
-  return line * 256 + (((((r & 3) << 2) | c) ^ (line & 3)) << 4);
-}
+// swizzle of row r: the 16-byte chunk c of the row sits in slot c ^ gswz(r) of the row's 128 bytes
+__device__ __forceinline__ int gswz(int r) { return ((r >> 1) & 3) | (((r >> 4) & 1) << 2); }
+// byte offset of 16-byte chunk c (0..7) of row r (0..255) inside a 256 x 64 operand tile
+__device__ __forceinline__ int gtile_off(int r, int c) { return r * 128 + ((c ^ gswz(r)) << 4); }
 
 template <typename G>
 __global__ __launch_bounds__(256, 1) void gemm_nt256_kernel(const uint16_t* __restrict__ x, int64_t ld_x,
@@ -210,7 +210,7 @@ __global__ __launch_bounds__(256, 1) void gemm_nt256_kernel(const uint16_t* __re
                                                             int64_t ld_y, float* __restrict__ y32, int M, int N, int K,
                                                             int tiles_n, int tiles_m, int groups_n) {
   typedef typename G::vec vec;
-  __shared__ __attribute__((aligned(1024))) uint8_t smem[kGStages * kGStage];
+  extern __shared__ __attribute__((aligned(1024))) uint8_t smem[];
   const int tid = threadIdx.x, lane = tid & 63, lr = lane & 31, hf = lane >> 5;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wi = wave & 1, wj = wave >> 1;
@@ -222,42 +222,43 @@ __global__ __launch_bounds__(256, 1) void gemm_nt256_kernel(const uint16_t* __re
   if (tn >= tiles_n || tm >= tiles_m) return;
   const int n0 = tn * GT, m0 = tm * GT;
 
-  // ---- staging: wave w moves lines 16w .. 16w+15 (rows 64w .. 64w+63) of both tiles, 4 lines per instruction
-  const int l4 = lane >> 4, slot = (lane & 15) ^ l4;          // the line index is congruent to l4 modulo 4
-  const int rr = 4 * l4 + (slot >> 2), sc = slot & 3;
-  uint32_t va[4], vb[4];
+  // ---- staging: wave w moves rows 64w .. 64w+63 of both tiles, 8 rows (8 whole 128-byte lines) per instruction;
+  //      lane l fills slot l % 8 of row l / 8 of the instruction's 1 KiB of LDS, i.e. fetches chunk slot ^ gswz(row)
+  uint32_t va[8], vb[8];
 #pragma unroll
-  for (int q = 0; q < 4; ++q) {
-    const int r = 64 * wave + 16 * q + rr;
+  for (int q = 0; q < 8; ++q) {
+    const int r = 64 * wave + 8 * q + (lane >> 3);
+    const int ch = (lane & 7) ^ gswz(r);
     const int n = n0 + r < N ? n0 + r : N - 1;                // clamped rows are never stored
     const int m = m0 + r < M ? m0 + r : M - 1;
-    va[q] = (uint32_t)(((int64_t)n * K + 8 * sc) * 2);
-    vb[q] = (uint32_t)(((int64_t)m * ld_x + 8 * sc) * 2);
+    va[q] = (uint32_t)(((int64_t)n * K + 8 * ch) * 2);
+    vb[q] = (uint32_t)(((int64_t)m * ld_x + 8 * ch) * 2);
   }
-  const uint32_t lds_wave = (uint32_t)(uintptr_t)(g_lds_u8*)smem + 4096u * (uint32_t)wave;
+  const uint32_t lds_wave = (uint32_t)(uintptr_t)(g_lds_u8*)smem + 8192u * (uint32_t)wave;
   const int nk = K / GK;
-  // one of the 8 direct loads of tile t: q = 0..3 the W^T tile, q = 4..7 the token tile
+  // one of the 16 direct loads of stage t: q = 0..7 the W^T tile, q = 8..15 the token tile
   auto issue_load = [&](int t, int q) {
     const int tk = t < nk ? t : nk - 1;                       // past the end: the last tile again, into a free stage
-    const uint32_t dst = lds_wave + (uint32_t)(t & (kGStages - 1)) * kGStage;
-    if (q < 4)
+    const uint32_t dst = lds_wave + (uint32_t)(t & 1) * kGStage;
+    if (q < 8)
       gload_lds16(wt + (int64_t)tk * GK, va[q], dst + 1024 * q);
     else
-      gload_lds16(x + (int64_t)tk * GK, vb[q - 4], dst + GT * GK * 2 + 1024 * (q - 4));
+      gload_lds16(x + (int64_t)tk * GK, vb[q - 8], dst + kGOperand + 1024 * (q - 8));
   };
 
-  // ---- fragments: A operand = rows of W^T in the permuted order that gives a lane 16 consecutive output
-  //      columns (row a of a 32-row tile is column 16*((a>>2)&1) + 4*(a>>3) + (a&3)); B operand = token rows
+  // ---- fragments: both operands take their 32 rows in the permuted order that gives a lane 16 consecutive output
+  //      columns (row a of a 32-row tile is column 16*((a>>2)&1) + 4*(a>>3) + (a&3)); for the token tile the
+  //      permutation only decides which token a lane ends up holding
   const int acol = (((lr >> 2) & 1) << 4) | ((lr >> 3) << 2) | (lr & 3);
   int offa[4], offb[4];
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
     offa[i] = gtile_off(128 * wi + 32 * i + acol, hf);
-    offb[i] = GT * GK * 2 + gtile_off(128 * wj + 32 * i + lr, hf);
+    offb[i] = kGOperand + gtile_off(128 * wj + 32 * i + acol, hf);
   }
-  // chunk 2*kk + hf of the row: bit 1 of the slot, bit 5 of the offset
+  // chunk 2*kk + hf of the row: bits 1, 2 of the slot, bits 5, 6 of the offset
   auto frag = [&](int t, int kk, int off) {
-    return *reinterpret_cast<const vec*>(smem + (t & (kGStages - 1)) * kGStage + (off ^ (kk << 5)));
+    return *reinterpret_cast<const vec*>(smem + (t & 1) * kGStage + (off ^ (kk << 5)));
   };
 
   f32x16 acc[4][4];
@@ -268,63 +269,62 @@ __global__ __launch_bounds__(256, 1) void gemm_nt256_kernel(const uint16_t* __re
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
-#pragma unroll
-  for (int t = 0; t < kGStages - 1; ++t)
-#pragma unroll
-    for (int q = 0; q < 8; ++q) issue_load(t, q);
-
   vec a0[4], b0[4], a1[4], b1[4];
-  for (int kt = 0; kt < nk; ++kt) {
-    // all but the newest tile's loads of this wave are complete, after the barrier everybody's: tiles kt and
-    // kt + 1 are in LDS; everybody is also done with tile kt - 1, whose stage takes tile kt + 3
-    __builtin_amdgcn_s_waitcnt(vmcnt_imm(kGLoads));
-    __syncthreads();
-    if (kt == 0) {
+  // One k step of 16: four groups of {two direct loads or none, the two fragment reads that the step after this
+  // one needs, four MFMAs}, fenced so that they stay in this order (a burst of loads holds the wave's in-order
+  // instruction stream, and with it the matrix pipe, for as long as the memory pipeline takes to accept them;
+  // measured: two loads per group over two steps; all sixteen in one step costs 5 %, waiting a stage later for
+  // them changes nothing - the stream's rate, not its latency, is what the loop feels).
+  auto kstep = [&](vec(&ca)[4], vec(&cb)[4], vec(&na)[4], vec(&nb)[4], int t_next, int kk_next, int t_load, int q0) {
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        a0[i] = frag(0, 0, offa[i]);
-        b0[i] = frag(0, 0, offb[i]);
+    for (int g = 0; g < 4; ++g) {
+      if (q0 >= 0) {
+#pragma unroll
+        for (int u = 0; u < 2; ++u) issue_load(t_load, q0 + 2 * g + u);
       }
-    }
-    // The iteration is eight groups of {one direct load of tile kt + 3, the two fragment reads that the step
-    // after this one needs, four MFMAs}, fenced so that they stay in this order: a burst of eight loads at the
-    // top of the iteration holds the wave's in-order instruction stream (and with it the matrix pipe) for as
-    // long as the memory pipeline takes to accept them.
-#pragma unroll
-    for (int g = 0; g < 4; ++g) {                             // k step 0 of tile kt; fetches k step 1
-      issue_load(kt + kGStages - 1, g);
       if (g < 2) {                                            // all token fragments first: the next step's first group needs them
-        b1[2 * g] = frag(kt, 1, offb[2 * g]);
-        b1[2 * g + 1] = frag(kt, 1, offb[2 * g + 1]);
+        nb[2 * g] = frag(t_next, kk_next, offb[2 * g]);
+        nb[2 * g + 1] = frag(t_next, kk_next, offb[2 * g + 1]);
       } else {
-        a1[2 * g - 4] = frag(kt, 1, offa[2 * g - 4]);
-        a1[2 * g - 3] = frag(kt, 1, offa[2 * g - 3]);
+        na[2 * g - 4] = frag(t_next, kk_next, offa[2 * g - 4]);
+        na[2 * g - 3] = frag(t_next, kk_next, offa[2 * g - 3]);
       }
 #pragma unroll
-      for (int j = 0; j < 4; ++j) acc[g][j] = G::mfma(a0[g], b0[j], acc[g][j]);
+      for (int j = 0; j < 4; ++j) acc[g][j] = G::mfma(ca[g], cb[j], acc[g][j]);
       __builtin_amdgcn_sched_barrier(0);
     }
+  };
+
+  // ---- prologue: stage 0 complete, the first half of stage 1 requested
 #pragma unroll
-    for (int g = 0; g < 4; ++g) {                             // k step 1 of tile kt; fetches k step 0 of tile kt + 1
-      issue_load(kt + kGStages - 1, 4 + g);
-      if (g < 2) {
-        b0[2 * g] = frag(kt + 1, 0, offb[2 * g]);
-        b0[2 * g + 1] = frag(kt + 1, 0, offb[2 * g + 1]);
-      } else {
-        a0[2 * g - 4] = frag(kt + 1, 0, offa[2 * g - 4]);
-        a0[2 * g - 3] = frag(kt + 1, 0, offa[2 * g - 3]);
-      }
+  for (int q = 0; q < 16; ++q) issue_load(0, q);
+  __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+  __syncthreads();
 #pragma unroll
-      for (int j = 0; j < 4; ++j) acc[g][j] = G::mfma(a1[g], b1[j], acc[g][j]);
-      __builtin_amdgcn_sched_barrier(0);
-    }
+  for (int q = 0; q < 8; ++q) issue_load(1, q);
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    a0[i] = frag(0, 0, offa[i]);
+    b0[i] = frag(0, 0, offb[i]);
+  }
+  for (int kt = 0; kt < nk; ++kt) {
+    // Stage kt is multiplied in four k steps.  The second half of stage kt + 1 is requested during the first step;
+    // before the last step the wave waits for its loads of stage kt + 1, and after the barrier everybody's have
+    // landed and everybody has read the last fragments of stage kt: the last step reads the first fragments of
+    // stage kt + 1 and requests the first half of stage kt + 2 into the buffer that stage kt leaves.
+    kstep(a0, b0, a1, b1, kt, 1, kt + 1, 8);
+    kstep(a1, b1, a0, b0, kt, 2, 0, -1);
+    kstep(a0, b0, a1, b1, kt, 3, 0, -1);
+    __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+    __syncthreads();
+    kstep(a1, b1, a0, b0, kt + 1, 0, kt + 2, 0);
   }
   __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));               // the look-ahead loads must land before the LDS is released
 
-  // lane (token lr of tile j, half hf) holds columns 16*hf .. 16*hf+15 of feature tile i
+  // lane (token acol of tile j, half hf) holds columns 16*hf .. 16*hf+15 of feature tile i
 #pragma unroll
   for (int j = 0; j < 4; ++j) {
-    const int m = m0 + 128 * wj + 32 * j + lr;
+    const int m = m0 + 128 * wj + 32 * j + acol;
     if (m >= M) continue;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
@@ -419,11 +419,19 @@ flp_status flp_launch_base_gemm(int dtype, const void* x, int64_t ld_x, const vo
     const int groups_n = (tiles_n + 3) / 4, groups_m = (tiles_m + 7) / 8;
     const int n_groups = (groups_n * groups_m + 7) / 8 * 8;
     dim3 grid256((unsigned)(n_groups * 32));
+    static bool attr_set = false;
+    if (!attr_set) {
+      FLP_TRY_HIP(hipFuncSetAttribute((const void*)gemm_nt256_kernel<GF16>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                      kGStages * kGStage));
+      FLP_TRY_HIP(hipFuncSetAttribute((const void*)gemm_nt256_kernel<GBF16>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                      kGStages * kGStage));
+      attr_set = true;
+    }
     if (dtype == FLP_F16)
-      hipLaunchKernelGGL(gemm_nt256_kernel<GF16>, grid256, dim3(256), 0, stream, xs, ld_x, ws, (uint16_t*)y, ld_y, y32, M,
+      hipLaunchKernelGGL(gemm_nt256_kernel<GF16>, grid256, dim3(256), kGStages * kGStage, stream, xs, ld_x, ws, (uint16_t*)y, ld_y, y32, M,
                          N, K, tiles_n, tiles_m, groups_n);
     else
-      hipLaunchKernelGGL(gemm_nt256_kernel<GBF16>, grid256, dim3(256), 0, stream, xs, ld_x, ws, (uint16_t*)y, ld_y, y32,
+      hipLaunchKernelGGL(gemm_nt256_kernel<GBF16>, grid256, dim3(256), kGStages * kGStage, stream, xs, ld_x, ws, (uint16_t*)y, ld_y, y32,
                          M, N, K, tiles_n, tiles_m, groups_n);
     FLP_TRY_HIP(hipGetLastError());
     return FLP_OK;

@@ -169,6 +169,38 @@ __global__ __launch_bounds__(64) void rmw_tile_kernel(uint16_t* __restrict__ y, 
   }
 }
 
+// The same 16 rows x 256 columns per step, but in a row-contiguous lane layout: an access instruction covers
+// 4 rows x 256 bytes (lane l: row 4q + l / 16, 16 bytes at column 8 (l % 16) of the 128-column half h), so
+// every group of 16 lanes touches two whole lines instead of sixteen partial ones.
+template <bool NT>
+__global__ __launch_bounds__(64) void rmw_tile_rows_kernel(uint16_t* __restrict__ y, int n_rows) {
+  const int lane = threadIdx.x;
+  for (int step = 0; step < 16; ++step) {
+    const int row0 = (blockIdx.x >> 4) * 256 + step * 16, slab = blockIdx.x & 15;
+    if (row0 >= n_rows) return;
+    u32x4* p[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const int row = row0 + 4 * q + (lane >> 4) < n_rows ? row0 + 4 * q + (lane >> 4) : n_rows - 1;
+      p[q] = reinterpret_cast<u32x4*>(y + (size_t)row * 4096 + 256 * slab + 8 * (lane & 15));
+    }
+    u32x4 r[2][4];
+#pragma unroll
+    for (int h = 0; h < 2; ++h)
+#pragma unroll
+      for (int q = 0; q < 4; ++q) r[h][q] = NT ? __builtin_nontemporal_load(p[q] + 16 * h) : p[q][16 * h];
+#pragma unroll
+    for (int h = 0; h < 2; ++h)
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        if (NT)
+          __builtin_nontemporal_store(r[h][q] + 1u, p[q] + 16 * h);
+        else
+          p[q][16 * h] = r[h][q] + 1u;
+      }
+  }
+}
+
 template <typename F>
 float best_ms(F launch) {
   hipEvent_t e0, e1;
@@ -239,6 +271,10 @@ int main() {
     std::printf("%-44s %8d %10.3f %12.2f\n", "tile update, wave keeps its 16 rows", g1, t, moved / t / 1e9);
     t = best_ms([&] { hipLaunchKernelGGL((rmw_tile_kernel<1, true>), dim3(g1), dim3(64), 0, 0, y, n_rows); });
     std::printf("%-44s %8d %10.3f %12.2f\n", "  same, non-temporal", g1, t, moved / t / 1e9);
+    t = best_ms([&] { hipLaunchKernelGGL((rmw_tile_rows_kernel<false>), dim3(g0), dim3(64), 0, 0, y, n_rows); });
+    std::printf("%-44s %8d %10.3f %12.2f\n", "tile update, 256 columns, row-contiguous lanes", g0, t, moved / t / 1e9);
+    t = best_ms([&] { hipLaunchKernelGGL((rmw_tile_rows_kernel<true>), dim3(g0), dim3(64), 0, 0, y, n_rows); });
+    std::printf("%-44s %8d %10.3f %12.2f\n", "  same, non-temporal", g0, t, moved / t / 1e9);
   }
   CHECK(hipFree(a));
   CHECK(hipFree(b));
