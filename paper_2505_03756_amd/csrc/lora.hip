@@ -384,17 +384,6 @@ __global__ __launch_bounds__(256) void lora_expand_rows_kernel(FlpLoraArgs a) {
   const int32_t* __restrict__ table = a.tables + pr.b_tab_off[ad];
   const int row0 = pr.b_row_base[ad];
   const int rpb = (int)(a.block_elems / pr.d_out);
-  // the first round's pieces of B are requested before the workgroup finds its tokens
-  const int rho_first = 8 * wave;
-  u32x4 raw8[8];
-  if (rho_first < r) {
-#pragma unroll
-    for (int k = 0; k < 8; ++k) {
-      const int row = row0 + (rho_first + k < r ? rho_first + k : r - 1);      // ranks past r repeat the last one, weight zero
-      raw8[k] = *reinterpret_cast<const u32x4*>(pool + (int64_t)table[row / rpb] * a.block_elems +
-                                                (int64_t)(row % rpb) * pr.d_out + colc);
-    }
-  }
   int tok[NTK] = {t, t, t, t};
   int n_tok = 1;
   if (share) {
@@ -413,14 +402,13 @@ __global__ __launch_bounds__(256) void lora_expand_rows_kernel(FlpLoraArgs a) {
   for (int j = 0; j < NTK; ++j)
 #pragma unroll
     for (int e = 0; e < EPL; ++e) acc[j][e] = 0.f;
-  for (int rho0 = rho_first; rho0 < r; rho0 += 32) {
-    if (rho0 != rho_first) {
+  for (int rho0 = 8 * wave; rho0 < r; rho0 += 32) {
+    u32x4 raw8[8];
 #pragma unroll
-      for (int k = 0; k < 8; ++k) {
-        const int row = row0 + (rho0 + k < r ? rho0 + k : r - 1);
-        raw8[k] = *reinterpret_cast<const u32x4*>(pool + (int64_t)table[row / rpb] * a.block_elems +
-                                                  (int64_t)(row % rpb) * pr.d_out + colc);
-      }
+    for (int k = 0; k < 8; ++k) {
+      const int row = row0 + (rho0 + k < r ? rho0 + k : r - 1);      // ranks past r repeat the last one, weight zero
+      raw8[k] = *reinterpret_cast<const u32x4*>(pool + (int64_t)table[row / rpb] * a.block_elems +
+                                                (int64_t)(row % rpb) * pr.d_out + colc);
     }
     float vv[NTK][8];
 #pragma unroll
