@@ -165,5 +165,9 @@ flp_status flp_launch_lora_simple(int dtype, const FlpLoraArgs& a, hipStream_t s
 flp_status flp_launch_base_gemm(int dtype, const void* x, int64_t ld_x, const void* w, int w_layout, void* y,
                                 int64_t ld_y, int M, int N, int K, void* wt_scratch, float* y32, float* splitk_scratch,
                                 size_t splitk_bytes, hipStream_t stream);
+// silu(x . Wg^T) * (x . Wu^T) in one pass (16-bit types, weights [N, K]); FLP_ENOTSUP, nothing launched, for shapes
+// that the large-batch kernel does not take
+flp_status flp_launch_gated_gemm(int dtype, const void* x, int64_t ld_x, const void* w_gate, const void* w_up,
+                                 void* out, int64_t ld_out, int M, int N, int K, hipStream_t stream);
 // bytes of split-K scratch worth offering for an [M, N] product (0 for large batches, which are not split)
 inline size_t flp_gemm_splitk_bytes(int M, int N) { return M <= 1024 ? (size_t)8 * M * N * 4 : 0; }

@@ -28,6 +28,7 @@ struct GF16 {
     return __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, c, 0, 0, 0);
   }
   static __device__ __forceinline__ uint16_t out(float f) { return F16::from_float(f); }
+  static __device__ __forceinline__ float in(uint16_t b) { return F16::to_float(b); }
 };
 struct GBF16 {
   typedef b16x8 vec;
@@ -35,6 +36,7 @@ struct GBF16 {
     return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
   }
   static __device__ __forceinline__ uint16_t out(float f) { return BF16::from_float(f); }
+  static __device__ __forceinline__ float in(uint16_t b) { return BF16::to_float(b); }
 };
 
 // ---- W [K, N] -> Wt [N, K], 16-bit elements, 64 x 64 tiles through LDS
@@ -204,11 +206,19 @@ __device__ __forceinline__ int gswz(int r) { return ((r >> 1) & 3) | (((r >> 4) 
 // byte offset of 16-byte chunk c (0..7) of row r (0..255) inside a 256 x 64 operand tile
 __device__ __forceinline__ int gtile_off(int r, int c) { return r * 128 + ((c ^ gswz(r)) << 4); }
 
-template <typename G>
+//
+// GATED: the gated-SiLU pair of an MLP in one pass.  The 256 feature rows of a tile are 128 rows of the gate
+// matrix (wt) and the same 128 rows of the up matrix (wt2): the waves with wi = 0 multiply the gate rows, those
+// with wi = 1 the up rows of the same features and tokens.  After the loop the up waves hand their accumulators
+// over through LDS (lane to lane: both layouts are the same) and the gate waves store silu(g) * u, with g and u rounded to the element type first, as the two separate products and
+// the element-wise kernel would have stored and re-read them.  Neither product is written.
+template <typename G, bool GATED>
 __global__ __launch_bounds__(256, 1) void gemm_nt256_kernel(const uint16_t* __restrict__ x, int64_t ld_x,
-                                                            const uint16_t* __restrict__ wt, uint16_t* __restrict__ y,
+                                                            const uint16_t* __restrict__ wt,
+                                                            const uint16_t* __restrict__ wt2, uint16_t* __restrict__ y,
                                                             int64_t ld_y, float* __restrict__ y32, int M, int N, int K,
                                                             int tiles_n, int tiles_m, int groups_n) {
+  constexpr int GTN = GATED ? GT / 2 : GT;              // output features per tile
   typedef typename G::vec vec;
   extern __shared__ __attribute__((aligned(1024))) uint8_t smem[];
   const int tid = threadIdx.x, lane = tid & 63, lr = lane & 31, hf = lane >> 5;
@@ -220,7 +230,8 @@ __global__ __launch_bounds__(256, 1) void gemm_nt256_kernel(const uint16_t* __re
   const int gid = (l >> 5) * 8 + xcd, within = l & 31;
   const int tn = (gid % groups_n) * 4 + (within & 3), tm = (gid / groups_n) * 8 + (within >> 2);
   if (tn >= tiles_n || tm >= tiles_m) return;
-  const int n0 = tn * GT, m0 = tm * GT;
+  const int n0 = tn * GTN, m0 = tm * GT;
+  const uint16_t* __restrict__ wsrc = GATED && wave >= 2 ? wt2 : wt;   // feature rows 128 .. 255 of a gated tile: the up matrix
 
   // ---- staging: wave w moves rows 64w .. 64w+63 of both tiles, 8 rows (8 whole 128-byte lines) per instruction;
   //      lane l fills slot l % 8 of row l / 8 of the instruction's 1 KiB of LDS, i.e. fetches chunk slot ^ gswz(row)
@@ -229,7 +240,8 @@ __global__ __launch_bounds__(256, 1) void gemm_nt256_kernel(const uint16_t* __re
   for (int q = 0; q < 8; ++q) {
     const int r = 64 * wave + 8 * q + (lane >> 3);
     const int ch = (lane & 7) ^ gswz(r);
-    const int n = n0 + r < N ? n0 + r : N - 1;                // clamped rows are never stored
+    const int rf = GATED ? (r & (GTN - 1)) : r;
+    const int n = n0 + rf < N ? n0 + rf : N - 1;              // clamped rows are never stored
     const int m = m0 + r < M ? m0 + r : M - 1;
     va[q] = (uint32_t)(((int64_t)n * K + 8 * ch) * 2);
     vb[q] = (uint32_t)(((int64_t)m * ld_x + 8 * ch) * 2);
@@ -241,7 +253,7 @@ __global__ __launch_bounds__(256, 1) void gemm_nt256_kernel(const uint16_t* __re
     const int tk = t < nk ? t : nk - 1;                       // past the end: the last tile again, into a free stage
     const uint32_t dst = lds_wave + (uint32_t)(t & 1) * kGStage;
     if (q < 8)
-      gload_lds16(wt + (int64_t)tk * GK, va[q], dst + 1024 * q);
+      gload_lds16(wsrc + (int64_t)tk * GK, va[q], dst + 1024 * q);
     else
       gload_lds16(x + (int64_t)tk * GK, vb[q - 8], dst + kGOperand + 1024 * (q - 8));
   };
@@ -321,6 +333,48 @@ __global__ __launch_bounds__(256, 1) void gemm_nt256_kernel(const uint16_t* __re
   }
   __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));               // the look-ahead loads must land before the LDS is released
 
+  if constexpr (GATED) {
+    // the up waves' 256 accumulator values per lane, [token half][value][lane] in the 128 KiB the stages leave
+    float* xch = reinterpret_cast<float*>(smem) + (wj * 256) * 64 + lane;
+    __syncthreads();                                       // everybody's loads have landed, nobody reads fragments any more
+    if (wi == 1) {
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+          for (int e = 0; e < 16; ++e) xch[((i * 4 + j) * 16 + e) * 64] = acc[i][j][e];
+    }
+    __syncthreads();
+    if (wi == 1) return;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int m = m0 + 128 * wj + 32 * j + acol;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int n = n0 + 32 * i + 16 * hf;
+        uint16_t o[16];
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+          const float g = G::in(G::out(acc[i][j][e])), u = G::in(G::out(xch[((i * 4 + j) * 16 + e) * 64]));
+          o[e] = G::out(g / (1.0f + expf(-g)) * u);
+        }
+        if (m >= M || n >= N) continue;
+        uint16_t* yp = y + (int64_t)m * ld_y + n;
+        if (n + 16 <= N) {
+          u32x4 raw[2];
+          __builtin_memcpy(raw, o, 32);
+          reinterpret_cast<u32x4*>(yp)[0] = raw[0];
+          reinterpret_cast<u32x4*>(yp)[1] = raw[1];
+        } else {
+          for (int e = 0; e < 16; ++e)
+            if (n + e < N) yp[e] = o[e];
+        }
+      }
+    }
+    return;
+  }
+
   // lane (token acol of tile j, half hf) holds columns 16*hf .. 16*hf+15 of feature tile i
 #pragma unroll
   for (int j = 0; j < 4; ++j) {
@@ -386,7 +440,51 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(const float* __restrict__
   y[(int64_t)m * ld_y + n] = acc;
 }
 
+flp_status gemm256_attrs() {
+  const void* fns[4] = {(const void*)gemm_nt256_kernel<GF16, false>, (const void*)gemm_nt256_kernel<GBF16, false>,
+                        (const void*)gemm_nt256_kernel<GF16, true>, (const void*)gemm_nt256_kernel<GBF16, true>};
+  for (const void* f : fns)
+    FLP_TRY_HIP(hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, kGStages * kGStage));
+  return FLP_OK;
+}
+
+// the shapes the 256 x 256 kernel takes: 32-bit byte offsets inside the operands, whole 64-coefficient stages
+bool gemm256_fits(int64_t M, int64_t n_rows_w, int64_t K, int64_t ld_x) {
+  return M >= 1024 && M * ld_x * 2 < ((int64_t)1 << 32) && n_rows_w * K * 2 < ((int64_t)1 << 32) && ld_x % 8 == 0 &&
+         K % GK == 0 && K / GK >= kGStages;
+}
+
 }  // namespace
+
+// out[M, N] = silu(x . Wg^T) * (x . Wu^T) with both matrices stored [N, K], 16-bit element types, in one pass of
+// the large-batch kernel (the two products are rounded to the element type before the gate is applied, as if
+// they had been stored).  Returns FLP_ENOTSUP without launching when the shape is one that the kernel does not
+// take (small batches, few tiles, offsets beyond 32 bits): the caller then runs the two products and the
+// element-wise step.
+flp_status flp_launch_gated_gemm(int dtype, const void* x, int64_t ld_x, const void* w_gate, const void* w_up,
+                                 void* out, int64_t ld_out, int M, int N, int K, hipStream_t stream) {
+  if (dtype != FLP_F16 && dtype != FLP_BF16) return FLP_ENOTSUP;
+  const int tiles_n = (N + GT / 2 - 1) / (GT / 2), tiles_m = (M + GT - 1) / GT;
+  if (M <= 0 || N < 128 || K <= 0 || !gemm256_fits(M, N, K, ld_x) || (int64_t)tiles_n * tiles_m < 96) return FLP_ENOTSUP;
+  static bool attr_set = false;
+  if (!attr_set) {
+    FLP_TRY(gemm256_attrs());
+    attr_set = true;
+  }
+  const int groups_n = (tiles_n + 3) / 4, groups_m = (tiles_m + 7) / 8;
+  const int n_groups = (groups_n * groups_m + 7) / 8 * 8;
+  dim3 grid((unsigned)(n_groups * 32));
+  if (dtype == FLP_F16)
+    hipLaunchKernelGGL((gemm_nt256_kernel<GF16, true>), grid, dim3(256), kGStages * kGStage, stream, (const uint16_t*)x,
+                       ld_x, (const uint16_t*)w_gate, (const uint16_t*)w_up, (uint16_t*)out, ld_out, (float*)nullptr, M, N,
+                       K, tiles_n, tiles_m, groups_n);
+  else
+    hipLaunchKernelGGL((gemm_nt256_kernel<GBF16, true>), grid, dim3(256), kGStages * kGStage, stream, (const uint16_t*)x,
+                       ld_x, (const uint16_t*)w_gate, (const uint16_t*)w_up, (uint16_t*)out, ld_out, (float*)nullptr, M, N,
+                       K, tiles_n, tiles_m, groups_n);
+  FLP_TRY_HIP(hipGetLastError());
+  return FLP_OK;
+}
 
 // y[M, N] = x[M, K] . W with w stored [K, N] (w_layout 0) or [N, K] (w_layout 1).  `wt_scratch` (16-bit
 // types with layout 0 only) must hold N*K elements; `y32` (16-bit types, optional) receives the
@@ -413,26 +511,22 @@ flp_status flp_launch_base_gemm(int dtype, const void* x, int64_t ld_x, const vo
   const uint16_t* ws = w_layout == 0 ? (const uint16_t*)wt_scratch : (const uint16_t*)w;
   // 32-bit byte offsets inside the operands and enough 256 x 256 tiles to occupy the chip (measured: with 64
   // tiles the 128 x 128 kernel is ahead, from 172 tiles on this one): the 256 x 256 kernel
-  if (M >= 1024 && N >= 256 && (int64_t)((M + GT - 1) / GT) * ((N + GT - 1) / GT) >= 96 && (int64_t)M * ld_x * 2 < ((int64_t)1 << 32) && (int64_t)N * K * 2 < ((int64_t)1 << 32) &&
-      ld_x % 8 == 0 && K / GK >= kGStages) {
+  if (N >= 256 && (int64_t)((M + GT - 1) / GT) * ((N + GT - 1) / GT) >= 96 && gemm256_fits(M, N, K, ld_x)) {
     const int tiles_n = (N + GT - 1) / GT, tiles_m = (M + GT - 1) / GT;
     const int groups_n = (tiles_n + 3) / 4, groups_m = (tiles_m + 7) / 8;
     const int n_groups = (groups_n * groups_m + 7) / 8 * 8;
     dim3 grid256((unsigned)(n_groups * 32));
     static bool attr_set = false;
     if (!attr_set) {
-      FLP_TRY_HIP(hipFuncSetAttribute((const void*)gemm_nt256_kernel<GF16>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                      kGStages * kGStage));
-      FLP_TRY_HIP(hipFuncSetAttribute((const void*)gemm_nt256_kernel<GBF16>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                      kGStages * kGStage));
+      FLP_TRY(gemm256_attrs());
       attr_set = true;
     }
     if (dtype == FLP_F16)
-      hipLaunchKernelGGL(gemm_nt256_kernel<GF16>, grid256, dim3(256), kGStages * kGStage, stream, xs, ld_x, ws, (uint16_t*)y, ld_y, y32, M,
-                         N, K, tiles_n, tiles_m, groups_n);
+      hipLaunchKernelGGL((gemm_nt256_kernel<GF16, false>), grid256, dim3(256), kGStages * kGStage, stream, xs, ld_x, ws,
+                         (const uint16_t*)nullptr, (uint16_t*)y, ld_y, y32, M, N, K, tiles_n, tiles_m, groups_n);
     else
-      hipLaunchKernelGGL(gemm_nt256_kernel<GBF16>, grid256, dim3(256), kGStages * kGStage, stream, xs, ld_x, ws, (uint16_t*)y, ld_y, y32,
-                         M, N, K, tiles_n, tiles_m, groups_n);
+      hipLaunchKernelGGL((gemm_nt256_kernel<GBF16, false>), grid256, dim3(256), kGStages * kGStage, stream, xs, ld_x, ws,
+                         (const uint16_t*)nullptr, (uint16_t*)y, ld_y, y32, M, N, K, tiles_n, tiles_m, groups_n);
     FLP_TRY_HIP(hipGetLastError());
     return FLP_OK;
   }

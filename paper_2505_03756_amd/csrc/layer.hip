@@ -392,12 +392,25 @@ extern "C" flp_status fll_layer_forward(flp_pool* p, const fll_layer_config* c, 
   }
   FLP_TRY(fll_add_rmsnorm(dtype, h, proj, w->post_norm, n, T, H, eps, hip_stream));
   {
-    const int which[2] = {4, 5}, d_outs[2] = {M, M};
-    void* const ys[2] = {gate, up};
-    const void* const ws[2] = {w->w_gate, w->w_up};
-    FLP_TRY(project(n, H, 2, which, ys, d_outs, ws));
+    // without LoRA branches on gate and up, and for a batch that the large-batch GEMM takes, the two products
+    // and the gate are one kernel that writes only silu(g) * u; otherwise two products and the element-wise step
+    const auto no_lora = [&](int i) {
+      const fll_lora_place& pl = b->lora[i];
+      return !pl.a_tab_off && !pl.a_row_base && !pl.b_tab_off && !pl.b_row_base;
+    };
+    flp_status fused = FLP_ENOTSUP;
+    if (no_lora(4) && no_lora(5))
+      fused = flp_launch_gated_gemm(dtype, n, H, w->w_gate, w->w_up, gate, M, T, M, H, (hipStream_t)hip_stream);
+    if (fused == FLP_ENOTSUP) {
+      const int which[2] = {4, 5}, d_outs[2] = {M, M};
+      void* const ys[2] = {gate, up};
+      const void* const ws[2] = {w->w_gate, w->w_up};
+      FLP_TRY(project(n, H, 2, which, ys, d_outs, ws));
+      FLP_TRY(fll_silu_mul(dtype, gate, M, up, M, gate, M, T, M, hip_stream));
+    } else if (fused != FLP_OK) {
+      return fused;
+    }
   }
-  FLP_TRY(fll_silu_mul(dtype, gate, M, up, M, gate, M, T, M, hip_stream));
   {
     const int which[1] = {6}, d_outs[1] = {H};
     void* const ys[1] = {proj};

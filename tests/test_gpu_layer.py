@@ -136,6 +136,12 @@ LAYER_CASES = {
     "bf16_attention_lora_only": lambda: layer_cfg("bf16", projections=("q", "k", "v", "o"), seed=45),
     # enough tokens for the matrix-core LoRA and attention kernels
     "f16_long": lambda: layer_cfg("f16", n_seqs=10, prefix_range=(0, 300), new_range=(100, 160), n_dev_blocks=2500, seed=44),
+    # over 1024 tokens, no LoRA on the MLP and 25 x 5 tiles of 128 features x 256 tokens: gate, up and the gated SiLU
+    # run as one pass of the large-batch GEMM (the last feature tile is half filled: 3136 = 24.5 x 128)
+    "f16_fused_gate_up": lambda: layer_cfg("f16", projections=("q", "k", "v", "o"), n_seqs=10, prefix_range=(0, 300),
+                                           new_range=(110, 160), mlp_dim=3136, n_dev_blocks=2500, seed=47),
+    "bf16_fused_gate_up": lambda: layer_cfg("bf16", projections=("q", "k", "v", "o"), n_seqs=10, prefix_range=(0, 300),
+                                            new_range=(110, 160), mlp_dim=3136, n_dev_blocks=2500, seed=48),
 }
 
 
