@@ -150,11 +150,18 @@ __global__ __launch_bounds__(256, 2) void gemm_nt_kernel(const uint16_t* __restr
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
       const int n = n0 + wn + 32 * i + 16 * hf;
-      if (y32) {
+      if (y32) {                                     // 64 contiguous bytes per lane where the row allows it
         float* yp32 = y32 + (int64_t)m * N + n;
+        if (n + 16 <= N && (N & 3) == 0) {
 #pragma unroll
-        for (int e = 0; e < 16; ++e)
-          if (n + e < N) yp32[e] = acc[i][j][e];
+          for (int e4 = 0; e4 < 4; ++e4) {
+            f32x4g v4 = {acc[i][j][4 * e4], acc[i][j][4 * e4 + 1], acc[i][j][4 * e4 + 2], acc[i][j][4 * e4 + 3]};
+            reinterpret_cast<f32x4g*>(yp32)[e4] = v4;
+          }
+        } else {
+          for (int e = 0; e < 16; ++e)
+            if (n + e < N) yp32[e] = acc[i][j][e];
+        }
       }
       if (!y) continue;                              // a slice of a split contraction writes only its partial
       uint16_t o[16];
