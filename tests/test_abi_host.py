@@ -217,3 +217,27 @@ def test_bench_refuses_more_than_one_gpu():
                        timeout=120)
     assert r.returncode == 2
     assert "ONE GPU" in r.stderr and r.stdout.strip() == ""
+
+
+def test_build_rejects_kernels_that_left_the_registers():
+    """The build parses the compiler's per-kernel resource report and stops when a kernel uses more than a few
+    spilled registers' worth of private memory (an accumulator array in scratch memory is many times slower and
+    fails no parity test): the parser on a report with one good and one bad kernel."""
+    from paper_2505_03756_amd import build as b
+    report = """
+x.hip:1:1: remark: Function Name: good_kernel [-Rpass-analysis=kernel-resource-usage]
+x.hip:1:1: remark:     VGPRs: 64 [-Rpass-analysis=kernel-resource-usage]
+x.hip:1:1: remark:     AGPRs: 0 [-Rpass-analysis=kernel-resource-usage]
+x.hip:1:1: remark:     ScratchSize [bytes/lane]: 56 [-Rpass-analysis=kernel-resource-usage]
+x.hip:1:1: remark:     Occupancy [waves/SIMD]: 8 [-Rpass-analysis=kernel-resource-usage]
+x.hip:1:1: remark:     LDS Size [bytes/block]: 1024 [-Rpass-analysis=kernel-resource-usage]
+x.hip:9:1: remark: Function Name: bad_kernel [-Rpass-analysis=kernel-resource-usage]
+x.hip:9:1: remark:     VGPRs: 103 [-Rpass-analysis=kernel-resource-usage]
+x.hip:9:1: remark:     AGPRs: 256 [-Rpass-analysis=kernel-resource-usage]
+x.hip:9:1: remark:     ScratchSize [bytes/lane]: 1088 [-Rpass-analysis=kernel-resource-usage]
+x.hip:9:1: remark:     Occupancy [waves/SIMD]: 1 [-Rpass-analysis=kernel-resource-usage]
+"""
+    res = b._resources(report)
+    assert res["good_kernel"] == {"vgprs": 64, "agprs": 0, "scratch": 56, "occupancy": 8, "lds": 1024}
+    assert res["bad_kernel"]["scratch"] == 1088 and res["bad_kernel"]["agprs"] == 256
+    assert [k for k, v in res.items() if v["scratch"] > b.MAX_SCRATCH_BYTES] == ["bad_kernel"]
