@@ -165,6 +165,14 @@ LORA_CASES = {
     "bf16_dense_tail": lambda: small_cfg("bf16", hidden=320, n_q_heads=5, n_kv_heads=1, head_dim=64, n_seqs=20,
                                          prefix_range=(0, 0), new_range=(40, 80), n_adapters=4, ranks=(16,),
                                          n_dev_blocks=1200, swap_in_frac=0.0, seed=88),
+    # enough 256 x 256 tiles (11 token rows x 9 feature columns; 9.5 columns in the bf16 case) for the large-batch GEMM
+    # when a dense base is given
+    "f16_dense_large": lambda: small_cfg("f16", hidden=512, n_q_heads=18, n_kv_heads=18, n_seqs=24, prefix_range=(0, 0),
+                                         new_range=(110, 160), n_adapters=6, ranks=(8, 16), n_dev_blocks=1500,
+                                         swap_in_frac=0.0, seed=89),
+    "bf16_dense_large_tail": lambda: small_cfg("bf16", hidden=512, n_q_heads=19, n_kv_heads=19, n_seqs=24,
+                                               prefix_range=(0, 0), new_range=(110, 160), n_adapters=6, ranks=(16, 32),
+                                               n_dev_blocks=1500, swap_in_frac=0.0, seed=90),
     "f16_rank64_gqa": lambda: small_cfg("f16", hidden=1024, n_q_heads=8, n_kv_heads=2, n_seqs=30,
                                         prefix_range=(0, 0), new_range=(30, 120), n_adapters=5, ranks=(64,),
                                         n_dev_blocks=1500, swap_in_frac=0.0, seed=84),
@@ -231,7 +239,8 @@ def test_lora_small_batches_share_adapter_pages(dtype, T):
         assert np.abs(want - base)[~none].max() > 0
 
 
-@pytest.mark.parametrize("name", ["tiny", "f16_prefill", "bf16_gqa_mixed", "f16_long_segments", "bf16_dense_tail"])
+@pytest.mark.parametrize("name", ["tiny", "f16_prefill", "bf16_gqa_mixed", "f16_long_segments", "bf16_dense_tail",
+                                  "f16_dense_large", "bf16_dense_large_tail"])
 def test_lora_with_dense_base(name):
     """w_base given: y = x.W_base + delta, the library computes the base term itself (Eq. 1's W)."""
     cfg = (CASES.get(name) or LORA_CASES[name])()
