@@ -203,6 +203,33 @@ def test_lora_matrix_core_shapes(name):
         assert err.max() <= ulp * (np.abs(want).max() + 1.0), (n, err.max())
 
 
+@pytest.mark.parametrize("names", [("q", "k"), ("q", "k", "v", "o"), ("v",)])
+def test_lora_call_with_one_two_or_four_projections(names):
+    """The staged shrink kernel of ranks up to 16 is compiled per number of projections in the call (they share x):
+    calls with 1, 2 and 4 projections on a batch long enough for the 32-token tiles (q, k, v together is covered
+    above).  All projections read the same x here, "o" included: the call does not care what x means."""
+    cfg = LORA_CASES["f16_long_segments"]()
+    step = wl.make_step(cfg)
+    assert step.n_tokens >= 2048 and int(step.rank.max()) <= 16 and cfg.hidden % 64 == 0
+    dev0 = resident_pool(step)
+    g = GpuStep(step, dev0, np.zeros((1, cfg.block_elems), dev0.dtype))
+    rtol, atol = TOL[cfg.dtype]
+    got = g.lora(list(names))
+    for n in names:
+        pr = step.proj[n]
+        assert pr.d_in == cfg.hidden
+        want = oracle.lora_apply(dev0, cfg.dtype, step.acts["x"], step.token_adapter, step.rank, step.scale,
+                                 pr.a_tab_off, pr.a_row_base, pr.b_tab_off, pr.b_row_base, step.lora_tables,
+                                 pr.d_out, y_in=step.acts["base_" + n])
+        ok, worst, nbad = close(wl.dequantize(got[n], cfg.dtype), want, rtol, atol)
+        assert ok, "%s: max err %g, %d elements out of tolerance" % (n, worst, nbad)
+        base = wl.dequantize(step.acts["base_" + n], cfg.dtype)
+        ulp = 2.0 ** -10
+        err = np.abs((wl.dequantize(got[n], cfg.dtype) - base) - (want - base))
+        assert err.max() <= ulp * (np.abs(want).max() + 1.0), (n, err.max())
+        assert np.abs(want - base).max() > 10 * atol
+
+
 @pytest.mark.parametrize("dtype,T", [("bf16", 1), ("bf16", 63), ("f32", 257), ("bf16", 1023), ("f16", 1024),
                                      ("f32", 1025)])
 def test_lora_small_batches_share_adapter_pages(dtype, T):
