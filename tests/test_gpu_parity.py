@@ -26,6 +26,7 @@ CASES = {
     "bf16_gqa_mixed": lambda: small_cfg("bf16", n_q_heads=8, n_kv_heads=2, hidden=1024, decode_frac=0.5,
                                         prefix_range=(0, 500), seed=79),
     "f16_d64": lambda: small_cfg("f16", head_dim=64, n_q_heads=8, n_kv_heads=8, seed=80),
+    "bf16_d64_gqa": lambda: small_cfg("bf16", head_dim=64, n_q_heads=8, n_kv_heads=4, decode_frac=0.4, seed=93),
     "f32_d128": lambda: small_cfg("f32", n_seqs=4, prefix_range=(0, 120), new_range=(1, 40), seed=81),
     # blocks of 32 token positions (the block size of the paper's vLLM baseline, section 2.2) as a layout variant:
     # prefill on the matrix-core kernel, decode / mixed and fp32 on the row kernel, head_dim 64
@@ -201,6 +202,29 @@ def test_lora_matrix_core_shapes(name):
         ulp = 2.0 ** (-10 if cfg.dtype == "f16" else -7)
         err = np.abs((wl.dequantize(got[n], cfg.dtype) - base) - (want - base))
         assert err.max() <= ulp * (np.abs(want).max() + 1.0), (n, err.max())
+
+
+@pytest.mark.parametrize("dtype,ranks", [("f16", (16,)), ("bf16", (8, 32, 64))])
+def test_lora_long_batch_with_input_width_not_a_multiple_of_64(dtype, ranks):
+    """32-token tiles (2048 tokens and more) with an input width of 288 = 9 x 32: the LDS-staged shrink kernels need
+    whole 64-coefficient chunks, so this batch takes the shrink kernel that reads its operands from global memory."""
+    cfg = small_cfg(dtype, hidden=288, n_q_heads=4, n_kv_heads=2, n_seqs=24, prefix_range=(0, 0), new_range=(90, 140),
+                    n_adapters=7, ranks=ranks, n_dev_blocks=1200, swap_in_frac=0.0, seed=94)
+    step = wl.make_step(cfg)
+    assert step.n_tokens >= 2048 and step.proj["q"].d_in == 288
+    dev0 = resident_pool(step)
+    g = GpuStep(step, dev0, np.zeros((1, cfg.block_elems), dev0.dtype))
+    rtol, atol = TOL[cfg.dtype]
+    got = g.lora(["q", "k", "v"])
+    for n in ("q", "k", "v"):
+        pr = step.proj[n]
+        want = oracle.lora_apply(dev0, cfg.dtype, step.acts["x"], step.token_adapter, step.rank, step.scale,
+                                 pr.a_tab_off, pr.a_row_base, pr.b_tab_off, pr.b_row_base, step.lora_tables,
+                                 pr.d_out, y_in=step.acts["base_" + n])
+        ok, worst, nbad = close(wl.dequantize(got[n], cfg.dtype), want, rtol, atol)
+        assert ok, "%s: max err %g, %d elements out of tolerance" % (n, worst, nbad)
+        base = wl.dequantize(step.acts["base_" + n], cfg.dtype)
+        assert np.abs(want - base).max() > 10 * atol
 
 
 @pytest.mark.parametrize("names", [("q", "k"), ("q", "k", "v", "o"), ("v",)])
