@@ -324,6 +324,13 @@ extern "C" flp_status flp_lora_apply_paged(flp_pool* p, const flp_lora_batch* b,
     const int rp = 16 * nt;
     v_elems = (size_t)ks * c.v_rows * b->n_proj * rp;
   }
+  // Dense base on every projection, and every product large enough for the large-batch GEMM: the expand step runs
+  // as that kernel's epilogue (segment, shrink, then one GEMM per projection that adds the LoRA branch to its
+  // accumulators before it rounds): no fp32 copy of the product, no second pass over y.
+  bool fused = mfma_ok;
+  for (int q = 0; q < b->n_proj; ++q)
+    fused = fused && b->proj[q].w_base &&
+            flp_gemm_is_large(p->cfg.dtype, b->n_tokens, b->proj[q].d_out, b->d_in, b->ld_x);
   size_t wt_bytes = 0;                         // transposed copy of the widest dense base matrix
   if (p->elem_bytes == 2)
     for (int q = 0; q < b->n_proj; ++q)
@@ -331,7 +338,7 @@ extern "C" flp_status flp_lora_apply_paged(flp_pool* p, const flp_lora_batch* b,
         wt_bytes = std::max(wt_bytes, (size_t)b->d_in * b->proj[q].d_out * 2);
   wt_bytes = (wt_bytes + 255) & ~(size_t)255;
   size_t base_bytes[FLP_MAX_PROJ] = {0, 0, 0, 0}, base_total = 0;   // unrounded base terms (16-bit pools)
-  if (p->elem_bytes == 2)
+  if (p->elem_bytes == 2 && !fused)
     for (int q = 0; q < b->n_proj; ++q)
       if (b->proj[q].w_base) {
         base_bytes[q] = (T * b->proj[q].d_out * 4 + 255) & ~(size_t)255;
@@ -345,8 +352,9 @@ extern "C" flp_status flp_lora_apply_paged(flp_pool* p, const flp_lora_batch* b,
   const size_t v_bytes = (v_elems * 4 + 255) & ~(size_t)255;
   const size_t seg_bytes = ((size_t)(4 * b->n_adapters + 5) * 4 + 255) & ~(size_t)255;
   const size_t perm_bytes = (T * 4 + 255) & ~(size_t)255;
+  const size_t inv_bytes = fused ? perm_bytes : 0;      // token -> position in segment order
   void* ws = nullptr;
-  FLP_TRY(flp_workspace(p, v_bytes + seg_bytes + perm_bytes + wt_bytes + base_total + splitk_bytes, &ws));
+  FLP_TRY(flp_workspace(p, v_bytes + seg_bytes + perm_bytes + wt_bytes + base_total + splitk_bytes + inv_bytes, &ws));
   FlpLoraArgs a{};
   a.pool = p->dev_base;
   a.block_elems = p->block_elems;
@@ -370,6 +378,44 @@ extern "C" flp_status flp_lora_apply_paged(flp_pool* p, const flp_lora_batch* b,
   a.tile_start = a.seg_start + b->n_adapters + 1;
   a.group_start = a.tile_start + b->n_adapters + 1;
   a.perm = (int32_t*)(w + v_bytes + seg_bytes);
+  if (fused) {
+    int32_t* inv_perm = (int32_t*)(w + v_bytes + seg_bytes + perm_bytes + wt_bytes + base_total + splitk_bytes);
+    uint8_t* wt = w + v_bytes + seg_bytes + perm_bytes;
+    FLP_TRY(flp_launch_lora_segment(a.T, a.token_adapter, a.n_adapters, a.n_seg, a.seg_adapter, a.seg_start, a.perm,
+                                    16 * c.mt, a.tile_start, c.group_tokens, a.group_start, stream, inv_perm));
+    c.shrink_only = 1;
+    FLP_TRY(flp_launch_lora_mfma(p->cfg.dtype, a, c, stream));
+    const int nt = (b->max_rank + 15) / 16 <= 2 ? (b->max_rank + 15) / 16 : 4;
+    for (int q = 0; q < b->n_proj; ++q) {
+      FlpGemmLora lp{};
+      lp.token_adapter = a.token_adapter;
+      lp.rank = a.rank;
+      lp.scale = a.scale;
+      lp.tables = a.tables;
+      lp.b_tab_off = b->proj[q].b_tab_off;
+      lp.b_row_base = b->proj[q].b_row_base;
+      lp.pool = a.pool;
+      lp.block_elems = a.block_elems;
+      lp.v = a.v;
+      lp.v_rows = c.v_rows;
+      lp.k_splits = c.k_splits;
+      lp.n_proj = b->n_proj;
+      lp.p = q;
+      lp.rp = 16 * nt;
+      lp.n_adapters = b->n_adapters;
+      lp.max_rank = b->max_rank < 16 * nt ? b->max_rank : 16 * nt;
+      lp.tm = 16 * c.mt;
+      lp.inv_perm = inv_perm;
+      lp.n_seg = a.n_seg;
+      lp.seg_adapter = a.seg_adapter;
+      lp.seg_start = a.seg_start;
+      lp.tile_start = a.tile_start;
+      FLP_TRY(flp_launch_base_gemm(p->cfg.dtype, b->x, b->ld_x, b->proj[q].w_base, b->proj[q].w_base_layout,
+                                   b->proj[q].y, b->proj[q].ld_y, b->n_tokens, b->proj[q].d_out, b->d_in, wt, nullptr,
+                                   nullptr, 0, stream, &lp));
+    }
+    return FLP_OK;
+  }
   // base term first where the caller asked for it (x . W_base), then the adapters' deltas on top.
   // 16-bit pools also keep the product unrounded in the workspace so that base + delta is rounded
   // once; tokens without an adapter keep the rounded value that the GEMM wrote into y.

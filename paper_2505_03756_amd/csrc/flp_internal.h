@@ -155,16 +155,44 @@ struct FlpLoraMfma {
   int32_t groups_bound;
   int32_t groups_grid;         // tile groups the expand launch covers in one pass (multiple of 8)
   int32_t slabs;               // column slabs per projection (set by the launcher)
+  int32_t shrink_only;         // 1: stop after the shrink step (the expand step runs inside the dense product)
+};
+
+// What the large-batch dense product needs to add one projection's LoRA branch to its accumulators before it
+// rounds (the expand step as an epilogue: y = round(x . W + s (x A^T) B), no fp32 copy of the product, no second
+// pass over y).  v is the shrink step's output, rows in segment order: token t of segment s sits in row
+// tile_start[s] * tm + inv_perm[t] - seg_start[s].
+struct FlpGemmLora {
+  const int32_t* token_adapter;
+  const int32_t* rank;
+  const float* scale;
+  const int32_t* tables;
+  const int32_t* b_tab_off;    // this projection's
+  const int32_t* b_row_base;
+  const void* pool;
+  int64_t block_elems;
+  const float* v;              // [k_splits][v_rows][n_proj][rp] fp32
+  int32_t v_rows, k_splits, n_proj, p, rp;
+  int32_t n_adapters, max_rank, tm;
+  const int32_t* inv_perm;     // [T] token -> position in segment order
+  const int32_t* n_seg;
+  const int32_t* seg_adapter;  // ascending adapter ids of the non-empty segments
+  const int32_t* seg_start;
+  const int32_t* tile_start;
 };
 
 flp_status flp_launch_lora_segment(int32_t T, const int32_t* token_adapter, int32_t n_adapters, int32_t* n_seg,
                                    int32_t* seg_adapter, int32_t* seg_start, int32_t* perm, int32_t tm,
-                                   int32_t* tile_start, int32_t tg, int32_t* group_start, hipStream_t stream);
+                                   int32_t* tile_start, int32_t tg, int32_t* group_start, hipStream_t stream,
+                                   int32_t* inv_perm = nullptr);
 flp_status flp_launch_lora_mfma(int dtype, const FlpLoraArgs& a, const FlpLoraMfma& c, hipStream_t stream);
 flp_status flp_launch_lora_simple(int dtype, const FlpLoraArgs& a, hipStream_t stream);
 flp_status flp_launch_base_gemm(int dtype, const void* x, int64_t ld_x, const void* w, int w_layout, void* y,
                                 int64_t ld_y, int M, int N, int K, void* wt_scratch, float* y32, float* splitk_scratch,
-                                size_t splitk_bytes, hipStream_t stream);
+                                size_t splitk_bytes, hipStream_t stream, const FlpGemmLora* lora = nullptr);
+// true when flp_launch_base_gemm runs the large-batch kernel for this shape (the one that can take the LoRA branch
+// as an epilogue)
+bool flp_gemm_is_large(int dtype, int M, int N, int K, int64_t ld_x);
 // silu(x . Wg^T) * (x . Wu^T) in one pass (16-bit types, weights [N, K]); FLP_ENOTSUP, nothing launched, for shapes
 // that the large-batch kernel does not take
 flp_status flp_launch_gated_gemm(int dtype, const void* x, int64_t ld_x, const void* w_gate, const void* w_up,

@@ -24,6 +24,7 @@ typedef __bf16 b16x8 __attribute__((ext_vector_type(8)));
 
 struct GF16 {
   typedef h16x8 vec;
+  typedef _Float16 elem;
   static __device__ __forceinline__ f32x16 mfma(vec a, vec b, f32x16 c) {
     return __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, c, 0, 0, 0);
   }
@@ -32,6 +33,7 @@ struct GF16 {
 };
 struct GBF16 {
   typedef b16x8 vec;
+  typedef __bf16 elem;
   static __device__ __forceinline__ f32x16 mfma(vec a, vec b, f32x16 c) {
     return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
   }
@@ -219,12 +221,19 @@ __device__ __forceinline__ int gtile_off(int r, int c) { return r * 128 + ((c ^ 
 // with wi = 1 the up rows of the same features and tokens.  After the loop the up waves hand their accumulators
 // over through LDS (lane to lane: both layouts are the same) and the gate waves store silu(g) * u, with g and u rounded to the element type first, as the two separate products and
 // the element-wise kernel would have stored and re-read them.  Neither product is written.
-template <typename G, bool GATED>
+//
+// LORA: the expand step of one projection's LoRA branch as an epilogue.  After the loop a wave holds the dense product
+// of its 128 tokens x 128 features; for every adapter among those tokens (tokens of a sequence are neighbours, so one
+// or two) it adds B^T (features x ranks, gathered from the adapter's pages in the A-operand layout of the same
+// permuted feature rows) times the tokens' scaled v (ranks x tokens, zero for tokens of other adapters; split into a
+// 16-bit high part and remainder, two MFMAs, so that v keeps its fp32 precision), 16 ranks per step, straight into
+// the accumulators.  The sum is rounded once; there is no fp32 copy of the product and no second pass over y.
+template <typename G, bool GATED, bool LORA>
 __global__ __launch_bounds__(256, 1) void gemm_nt256_kernel(const uint16_t* __restrict__ x, int64_t ld_x,
                                                             const uint16_t* __restrict__ wt,
                                                             const uint16_t* __restrict__ wt2, uint16_t* __restrict__ y,
                                                             int64_t ld_y, float* __restrict__ y32, int M, int N, int K,
-                                                            int tiles_n, int tiles_m, int groups_n) {
+                                                            int tiles_n, int tiles_m, int groups_n, FlpGemmLora lp) {
   constexpr int GTN = GATED ? GT / 2 : GT;              // output features per tile
   typedef typename G::vec vec;
   extern __shared__ __attribute__((aligned(1024))) uint8_t smem[];
@@ -382,6 +391,99 @@ __global__ __launch_bounds__(256, 1) void gemm_nt256_kernel(const uint16_t* __re
     return;
   }
 
+  if constexpr (LORA) {
+    typedef typename G::elem elem;
+    const uint16_t* __restrict__ pool = reinterpret_cast<const uint16_t*>(lp.pool);
+    const int n_seg = *lp.n_seg;
+    const int rpb = (int)(lp.block_elems / N);
+    int adj[4], posj[4];                                  // adapter and segment-order position of the lane's four tokens
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int m = m0 + 128 * wj + 32 * j + acol;
+      int ad = m < M ? lp.token_adapter[m] : -1;
+      if (ad >= lp.n_adapters) ad = -1;
+      adj[j] = ad;
+      posj[j] = ad >= 0 ? lp.inv_perm[m] : 0;
+    }
+    for (;;) {
+      int cand = -1;
+#pragma unroll
+      for (int j = 3; j >= 0; --j) cand = adj[j] >= 0 ? adj[j] : cand;
+      const uint64_t todo = __ballot(cand >= 0);
+      if (!todo) break;
+      const int ad = __builtin_amdgcn_readlane(cand, __ffsll((long long)todo) - 1);      // wave-uniform
+      const int r = lp.rank[ad] < lp.max_rank ? lp.rank[ad] : lp.max_rank;
+      if (r > 0) {
+        const float sc = lp.scale[ad];
+        int lo = 0, hi = n_seg;                               // the adapter's segment: seg_adapter is ascending
+        while (hi - lo > 1) {
+          const int mid = (lo + hi) >> 1;
+          if (lp.seg_adapter[mid] <= ad) lo = mid; else hi = mid;
+        }
+        const int64_t vrow0 = (int64_t)lp.tile_start[lo] * lp.tm - lp.seg_start[lo];
+        const int32_t* __restrict__ tab = lp.tables + lp.b_tab_off[ad];
+        const int brow0 = lp.b_row_base[ad];
+        for (int nt = 0; 16 * nt < r; ++nt) {
+          // A operand: B[rho, feature] for the lane's 8 ranks and its feature row of each of the four feature tiles
+          const uint16_t* rowp[8];
+#pragma unroll
+          for (int q = 0; q < 8; ++q) {
+            const int rho = 16 * nt + 8 * hf + q;
+            const int row = brow0 + (rho < r ? rho : 0);
+            rowp[q] = pool + (int64_t)tab[row / rpb] * lp.block_elems + (int64_t)(row % rpb) * N;
+          }
+          vec af[4];
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            const int f = n0 + 128 * wi + 32 * i + acol;
+            const int fc = f < N ? f : N - 1;
+            uint16_t g8[8];
+#pragma unroll
+            for (int q = 0; q < 8; ++q) g8[q] = rowp[q][fc];
+#pragma unroll
+            for (int q = 0; q < 8; ++q)
+              if (!(16 * nt + 8 * hf + q < r && f < N)) g8[q] = 0;
+            __builtin_memcpy(&af[i], g8, 16);
+          }
+          // B operand: the tokens' scaled v for those 8 ranks, zero for tokens of other adapters
+#pragma unroll
+          for (int j = 0; j < 4; ++j) {
+            float v8[8];
+#pragma unroll
+            for (int q = 0; q < 8; ++q) v8[q] = 0.f;
+            if (adj[j] == ad) {
+              for (int ks = 0; ks < lp.k_splits; ++ks) {
+                const float* vp = lp.v + (((int64_t)ks * lp.v_rows + vrow0 + posj[j]) * lp.n_proj + lp.p) * lp.rp +
+                                  16 * nt + 8 * hf;
+                const f32x4g x0 = *reinterpret_cast<const f32x4g*>(vp), x1 = *reinterpret_cast<const f32x4g*>(vp + 4);
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                  v8[q] += x0[q];
+                  v8[4 + q] += x1[q];
+                }
+              }
+            }
+            vec bh, bl;
+#pragma unroll
+            for (int q = 0; q < 8; ++q) {
+              const float vs = v8[q] * sc;
+              const elem h = (elem)vs;
+              bh[q] = h;
+              bl[q] = (elem)(vs - (float)h);
+            }
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+              acc[i][j] = G::mfma(af[i], bh, acc[i][j]);
+              acc[i][j] = G::mfma(af[i], bl, acc[i][j]);
+            }
+          }
+        }
+      }
+#pragma unroll
+      for (int j = 0; j < 4; ++j) adj[j] = adj[j] == ad ? -1 : adj[j];
+    }
+  }
+
   // lane (token acol of tile j, half hf) holds columns 16*hf .. 16*hf+15 of feature tile i
 #pragma unroll
   for (int j = 0; j < 4; ++j) {
@@ -448,8 +550,9 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(const float* __restrict__
 }
 
 flp_status gemm256_attrs() {
-  const void* fns[4] = {(const void*)gemm_nt256_kernel<GF16, false>, (const void*)gemm_nt256_kernel<GBF16, false>,
-                        (const void*)gemm_nt256_kernel<GF16, true>, (const void*)gemm_nt256_kernel<GBF16, true>};
+  const void* fns[6] = {(const void*)gemm_nt256_kernel<GF16, false, false>, (const void*)gemm_nt256_kernel<GBF16, false, false>,
+                        (const void*)gemm_nt256_kernel<GF16, true, false>, (const void*)gemm_nt256_kernel<GBF16, true, false>,
+                        (const void*)gemm_nt256_kernel<GF16, false, true>, (const void*)gemm_nt256_kernel<GBF16, false, true>};
   for (const void* f : fns)
     FLP_TRY_HIP(hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, kGStages * kGStage));
   return FLP_OK;
@@ -482,15 +585,20 @@ flp_status flp_launch_gated_gemm(int dtype, const void* x, int64_t ld_x, const v
   const int n_groups = (groups_n * groups_m + 7) / 8 * 8;
   dim3 grid((unsigned)(n_groups * 32));
   if (dtype == FLP_F16)
-    hipLaunchKernelGGL((gemm_nt256_kernel<GF16, true>), grid, dim3(256), kGStages * kGStage, stream, (const uint16_t*)x,
-                       ld_x, (const uint16_t*)w_gate, (const uint16_t*)w_up, (uint16_t*)out, ld_out, (float*)nullptr, M, N,
-                       K, tiles_n, tiles_m, groups_n);
+    hipLaunchKernelGGL((gemm_nt256_kernel<GF16, true, false>), grid, dim3(256), kGStages * kGStage, stream,
+                       (const uint16_t*)x, ld_x, (const uint16_t*)w_gate, (const uint16_t*)w_up, (uint16_t*)out, ld_out,
+                       (float*)nullptr, M, N, K, tiles_n, tiles_m, groups_n, FlpGemmLora{});
   else
-    hipLaunchKernelGGL((gemm_nt256_kernel<GBF16, true>), grid, dim3(256), kGStages * kGStage, stream, (const uint16_t*)x,
-                       ld_x, (const uint16_t*)w_gate, (const uint16_t*)w_up, (uint16_t*)out, ld_out, (float*)nullptr, M, N,
-                       K, tiles_n, tiles_m, groups_n);
+    hipLaunchKernelGGL((gemm_nt256_kernel<GBF16, true, false>), grid, dim3(256), kGStages * kGStage, stream,
+                       (const uint16_t*)x, ld_x, (const uint16_t*)w_gate, (const uint16_t*)w_up, (uint16_t*)out, ld_out,
+                       (float*)nullptr, M, N, K, tiles_n, tiles_m, groups_n, FlpGemmLora{});
   FLP_TRY_HIP(hipGetLastError());
   return FLP_OK;
+}
+
+bool flp_gemm_is_large(int dtype, int M, int N, int K, int64_t ld_x) {
+  return (dtype == FLP_F16 || dtype == FLP_BF16) && N >= 256 &&
+         (int64_t)((M + GT - 1) / GT) * ((N + GT - 1) / GT) >= 96 && gemm256_fits(M, N, K, ld_x);
 }
 
 // y[M, N] = x[M, K] . W with w stored [K, N] (w_layout 0) or [N, K] (w_layout 1).  `wt_scratch` (16-bit
@@ -498,8 +606,12 @@ flp_status flp_launch_gated_gemm(int dtype, const void* x, int64_t ld_x, const v
 // unrounded product as dense fp32 [M, N].
 flp_status flp_launch_base_gemm(int dtype, const void* x, int64_t ld_x, const void* w, int w_layout, void* y,
                                 int64_t ld_y, int M, int N, int K, void* wt_scratch, float* y32, float* splitk_scratch,
-                                size_t splitk_bytes, hipStream_t stream) {
+                                size_t splitk_bytes, hipStream_t stream, const FlpGemmLora* lora) {
   if (M <= 0 || N <= 0 || K <= 0) return FLP_OK;
+  if (lora && !flp_gemm_is_large(dtype, M, N, K, ld_x)) {
+    flp_set_error("base GEMM: the LoRA epilogue needs the large-batch kernel (M=%d N=%d K=%d)", M, N, K);
+    return FLP_ENOTSUP;
+  }
   if (dtype == FLP_F32) {
     hipLaunchKernelGGL(gemm_f32_kernel, dim3((N + 255) / 256, M), dim3(256), 0, stream, (const float*)x, ld_x,
                        (const float*)w, w_layout ? (int64_t)1 : (int64_t)N, w_layout ? (int64_t)K : (int64_t)1, (float*)y,
@@ -518,7 +630,7 @@ flp_status flp_launch_base_gemm(int dtype, const void* x, int64_t ld_x, const vo
   const uint16_t* ws = w_layout == 0 ? (const uint16_t*)wt_scratch : (const uint16_t*)w;
   // 32-bit byte offsets inside the operands and enough 256 x 256 tiles to occupy the chip (measured: with 64
   // tiles the 128 x 128 kernel is ahead, from 172 tiles on this one): the 256 x 256 kernel
-  if (N >= 256 && (int64_t)((M + GT - 1) / GT) * ((N + GT - 1) / GT) >= 96 && gemm256_fits(M, N, K, ld_x)) {
+  if (flp_gemm_is_large(dtype, M, N, K, ld_x)) {
     const int tiles_n = (N + GT - 1) / GT, tiles_m = (M + GT - 1) / GT;
     const int groups_n = (tiles_n + 3) / 4, groups_m = (tiles_m + 7) / 8;
     const int n_groups = (groups_n * groups_m + 7) / 8 * 8;
@@ -528,12 +640,19 @@ flp_status flp_launch_base_gemm(int dtype, const void* x, int64_t ld_x, const vo
       FLP_TRY(gemm256_attrs());
       attr_set = true;
     }
-    if (dtype == FLP_F16)
-      hipLaunchKernelGGL((gemm_nt256_kernel<GF16, false>), grid256, dim3(256), kGStages * kGStage, stream, xs, ld_x, ws,
-                         (const uint16_t*)nullptr, (uint16_t*)y, ld_y, y32, M, N, K, tiles_n, tiles_m, groups_n);
+    const uint16_t* none = nullptr;
+    if (lora && dtype == FLP_F16)
+      hipLaunchKernelGGL((gemm_nt256_kernel<GF16, false, true>), grid256, dim3(256), kGStages * kGStage, stream, xs, ld_x,
+                         ws, none, (uint16_t*)y, ld_y, y32, M, N, K, tiles_n, tiles_m, groups_n, *lora);
+    else if (lora)
+      hipLaunchKernelGGL((gemm_nt256_kernel<GBF16, false, true>), grid256, dim3(256), kGStages * kGStage, stream, xs, ld_x,
+                         ws, none, (uint16_t*)y, ld_y, y32, M, N, K, tiles_n, tiles_m, groups_n, *lora);
+    else if (dtype == FLP_F16)
+      hipLaunchKernelGGL((gemm_nt256_kernel<GF16, false, false>), grid256, dim3(256), kGStages * kGStage, stream, xs, ld_x,
+                         ws, none, (uint16_t*)y, ld_y, y32, M, N, K, tiles_n, tiles_m, groups_n, FlpGemmLora{});
     else
-      hipLaunchKernelGGL((gemm_nt256_kernel<GBF16, false>), grid256, dim3(256), kGStages * kGStage, stream, xs, ld_x, ws,
-                         (const uint16_t*)nullptr, (uint16_t*)y, ld_y, y32, M, N, K, tiles_n, tiles_m, groups_n);
+      hipLaunchKernelGGL((gemm_nt256_kernel<GBF16, false, false>), grid256, dim3(256), kGStages * kGStage, stream, xs,
+                         ld_x, ws, none, (uint16_t*)y, ld_y, y32, M, N, K, tiles_n, tiles_m, groups_n, FlpGemmLora{});
     FLP_TRY_HIP(hipGetLastError());
     return FLP_OK;
   }

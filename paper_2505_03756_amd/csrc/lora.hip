@@ -24,7 +24,8 @@ __global__ __launch_bounds__(1024) void lora_segment_kernel(int32_t T, const int
                                                             int32_t* __restrict__ seg_start,
                                                             int32_t* __restrict__ perm, int32_t tm,
                                                             int32_t* __restrict__ tile_start, int32_t tg,
-                                                            int32_t* __restrict__ group_start) {
+                                                            int32_t* __restrict__ group_start,
+                                                            int32_t* __restrict__ inv_perm) {
   extern __shared__ int32_t sm[];
   int32_t* whist = sm;                         // [kSegWaves][n_ad]: counts, then running cursors
   int32_t* tot = sm + kSegWaves * n_ad;        // [n_ad] tokens per adapter
@@ -181,7 +182,11 @@ __global__ __launch_bounds__(1024) void lora_segment_kernel(int32_t T, const int
         const int v = __shfl(a, leader);
         const uint64_t same = __ballot(valid && a == v);
         const int before = cur[v];
-        if (valid && a == v) perm[seg_off[v] + before + __popcll(same & ((1ull << lane) - 1))] = t;
+        if (valid && a == v) {
+          const int pos = seg_off[v] + before + __popcll(same & ((1ull << lane) - 1));
+          perm[pos] = t;
+          if (inv_perm) inv_perm[t] = pos;
+        }
         __builtin_amdgcn_wave_barrier();
         if (lane == leader) cur[v] = before + __popcll(same);
         __builtin_amdgcn_wave_barrier();
@@ -459,7 +464,8 @@ __global__ __launch_bounds__(256) void lora_expand_rows_kernel(FlpLoraArgs a) {
 
 flp_status flp_launch_lora_segment(int32_t T, const int32_t* token_adapter, int32_t n_adapters, int32_t* n_seg,
                                    int32_t* seg_adapter, int32_t* seg_start, int32_t* perm, int32_t tm,
-                                   int32_t* tile_start, int32_t tg, int32_t* group_start, hipStream_t stream) {
+                                   int32_t* tile_start, int32_t tg, int32_t* group_start, hipStream_t stream,
+                                   int32_t* inv_perm) {
   const size_t smem = ((size_t)(kSegWaves + 2) * (size_t)(n_adapters > 0 ? n_adapters : 1) + 4 * kSegWaves + 4) * 4;
   static bool attr_set = false;
   if (!attr_set) {
@@ -468,7 +474,7 @@ flp_status flp_launch_lora_segment(int32_t T, const int32_t* token_adapter, int3
     attr_set = true;
   }
   hipLaunchKernelGGL(lora_segment_kernel, dim3(1), dim3(1024), smem, stream, T, token_adapter, n_adapters, n_seg,
-                     seg_adapter, seg_start, perm, tm, tile_start, tg, group_start);
+                     seg_adapter, seg_start, perm, tm, tile_start, tg, group_start, inv_perm);
   FLP_TRY_HIP(hipGetLastError());
   return FLP_OK;
 }

@@ -783,6 +783,7 @@ flp_status launch_pair(const FlpLoraArgs& a, const FlpLoraMfma& c, hipStream_t s
     hipLaunchKernelGGL((lora_shrink_mfma_kernel<L, MT, NT, ONEP>),
                        dim3((unsigned)(c.tiles_grid * c.k_splits * (ONEP ? a.n_proj : 1))), dim3(256), smem, stream, a, c);
   FLP_TRY_HIP(hipGetLastError());
+  if (c.shrink_only) return FLP_OK;                     // the expand step is the dense product's epilogue
   int max_dout = 0;
   for (int p = 0; p < a.n_proj; ++p) max_dout = a.proj[p].d_out > max_dout ? a.proj[p].d_out : max_dout;
   FlpLoraMfma ce = c;

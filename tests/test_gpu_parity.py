@@ -304,7 +304,11 @@ def test_lora_with_dense_base(name):
     W = {n: wl.quantize((rng.standard_normal((cfg.hidden, step.proj[n].d_out)) / np.sqrt(cfg.hidden)).astype(np.float32),
                         cfg.dtype) for n in names}
     got = g.lora(names, w_base={n: to_dev(W[n]) for n in names})
-    sel = np.sort(rng.choice(step.n_tokens, size=min(step.n_tokens, 64), replace=False)).astype(np.int32)
+    # a random sample, both ends of every sequence (where the adapter changes inside a tile) and the end of the batch
+    T = step.n_tokens
+    sel = np.unique(np.concatenate([rng.choice(T, size=min(T, 64), replace=False), step.cu_new[:-1],
+                                    step.cu_new[1:] - 1, np.arange(max(0, T - 40), T)])).astype(np.int32)
+    sel = sel[(sel >= 0) & (sel < T)]
     for n in names:
         pr = step.proj[n]
         want = oracle.lora_apply(dev0, cfg.dtype, step.acts["x"], step.token_adapter, step.rank, step.scale,
