@@ -327,7 +327,9 @@ extern "C" flp_status flp_lora_apply_paged(flp_pool* p, const flp_lora_batch* b,
   // Dense base on every projection, and every product large enough for the large-batch GEMM: the expand step runs
   // as that kernel's epilogue (segment, shrink, then one GEMM per projection that adds the LoRA branch to its
   // accumulators before it rounds): no fp32 copy of the product, no second pass over y.
-  bool fused = mfma_ok;
+  // (Batches of 2048 tokens and more only: the epilogue walks the adapters present among a wave's 128 tokens, which
+  // are one or two when tokens come in sequences and up to 128 in a large pure-decode batch.)
+  bool fused = mfma_ok && b->n_tokens >= 2048;
   for (int q = 0; q < b->n_proj; ++q)
     fused = fused && b->proj[q].w_base &&
             flp_gemm_is_large(p->cfg.dtype, b->n_tokens, b->proj[q].d_out, b->d_in, b->ld_x);

@@ -297,6 +297,14 @@ def test_lora_with_dense_base(name):
     cfg = (CASES.get(name) or LORA_CASES[name])()
     step = wl.make_step(cfg)
     rng = np.random.default_rng(55)
+    if "large" in name:
+        # tokens without an adapter inside the batch: one whole sequence, and single tokens inside other sequences
+        # (the LoRA branch is added inside the GEMM there, per adapter present among a wave's 128 tokens)
+        ta = step.token_adapter.copy()
+        ta[step.cu_new[3]:step.cu_new[4]] = -1
+        ta[rng.choice(step.n_tokens, size=50, replace=False)] = -1
+        ta[step.cu_new[7] + 5:step.cu_new[7] + 9] = step.token_adapter[step.cu_new[9]]   # another sequence's adapter mid-sequence
+        step.token_adapter = ta
     dev0 = resident_pool(step)
     g = GpuStep(step, dev0, np.zeros((1, cfg.block_elems), dev0.dtype))
     rtol, atol = TOL[cfg.dtype]
@@ -308,6 +316,9 @@ def test_lora_with_dense_base(name):
     T = step.n_tokens
     sel = np.unique(np.concatenate([rng.choice(T, size=min(T, 64), replace=False), step.cu_new[:-1],
                                     step.cu_new[1:] - 1, np.arange(max(0, T - 40), T)])).astype(np.int32)
+    if "large" in name:
+        sel = np.unique(np.concatenate([sel, np.flatnonzero(step.token_adapter < 0)[:60],
+                                        np.arange(step.cu_new[7], step.cu_new[7] + 12)])).astype(np.int32)
     sel = sel[(sel >= 0) & (sel < T)]
     for n in names:
         pr = step.proj[n]
