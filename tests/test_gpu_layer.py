@@ -140,6 +140,11 @@ LAYER_CASES = {
     # run as one pass of the large-batch GEMM (the last feature tile is half filled: 3136 = 24.5 x 128)
     "f16_fused_gate_up": lambda: layer_cfg("f16", projections=("q", "k", "v", "o"), n_seqs=10, prefix_range=(0, 300),
                                            new_range=(110, 160), mlp_dim=3136, n_dev_blocks=2500, seed=47),
+    # 3000 tokens and more, hidden 2048: 12 x 8 tiles of 256 x 256 for q, k, v, o, so the LoRA branch of those
+    # projections is added inside the large-batch GEMM (weights as [d_out, d_in]); down takes the plain large-batch GEMM
+    "f16_lora_inside_gemm": lambda: layer_cfg("f16", hidden=2048, n_q_heads=16, n_kv_heads=16,
+                                              projections=("q", "k", "v", "o"), n_seqs=24, prefix_range=(0, 200),
+                                              new_range=(125, 150), mlp_dim=3136, n_dev_blocks=2500, seed=49),
     "bf16_fused_gate_up": lambda: layer_cfg("bf16", projections=("q", "k", "v", "o"), n_seqs=10, prefix_range=(0, 300),
                                             new_range=(110, 160), mlp_dim=3136, n_dev_blocks=2500, seed=48),
 }
