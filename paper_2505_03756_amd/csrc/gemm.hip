@@ -1,14 +1,17 @@
-// Base projection y = x . W_base for flp_lora_apply_paged when the caller passes w_base
-// (paper Eq. 1: W' = W + A B; this is the W term.  The paper keeps the base model outside the
-// pool, and so does this library: w_base is an ordinary dense [d_in, d_out] matrix).
+// Dense products of the layer step: the base projection y = x . W_base of flp_lora_apply_paged when the caller
+// passes w_base (paper Eq. 1: W' = W + A B; this is the W term.  The paper keeps the base model outside the pool,
+// and so does this library: w_base is an ordinary dense matrix, [d_in, d_out] or [d_out, d_in]), and the dense
+// projections of fll_layer_forward.
 //
-// 16-bit pools: W is first transposed into the pool's workspace ([d_out, d_in], so that both
-// operands are contiguous along the contraction), then a tiled MFMA GEMM runs: 128 x 128 output
-// tile per workgroup (4 waves, 64 x 64 each, mfma_f32_32x32x16), 64-deep k tiles staged through
-// LDS (XOR-swizzled 16-byte chunks, double buffered, next tile prefetched through registers).
-// The product is computed transposed (A operand = rows of W^T, B operand = token rows) and the
-// rows of W^T are fed in a permuted order so that a lane ends up with 16 consecutive output
-// columns of one token: y is written in 32-byte pieces.
+// 16-bit pools: both operands are read along the contraction (a W given as [d_in, d_out] is first transposed into
+// the pool's workspace).  Two tiled MFMA kernels, both computing the product transposed (A operand = rows of W^T,
+// B operand = token rows) with the rows of W^T fed in a permuted order, so that a lane ends up with 16 consecutive
+// output columns of one token and y is written in 32-byte pieces:
+//   gemm_nt_kernel      128 x 128 tile, 4 waves x (64 x 64), k tiles of 64 through LDS with the next tile prefetched
+//                       through registers; small batches, with the contraction split over grid z when tiles are few;
+//   gemm_nt256_kernel   256 x 256 tile, 4 waves x (128 x 128), operands streamed by direct global-to-LDS loads; large
+//                       batches.  Two epilogue variants: GATED (gate and up of an MLP in one pass, silu(g) * u stored)
+//                       and LORA (the expand step of the projection's LoRA branch added to the accumulators).
 // fp32 pools: a plain one-thread-per-output kernel (the fp32 workload is tiny).
 #include <hip/hip_runtime.h>
 
