@@ -234,7 +234,25 @@ extern "C" flp_status flp_lora_segment(flp_pool* p, int32_t n_tokens, const int3
                                  nullptr, (hipStream_t)hip_stream);
 }
 
+namespace {
+flp_status lora_apply_impl(flp_pool* p, const flp_lora_batch* b, void* hip_stream, void* gated_out, int64_t ld_gated);
+}
+
 extern "C" flp_status flp_lora_apply_paged(flp_pool* p, const flp_lora_batch* b, void* hip_stream) {
+  return lora_apply_impl(p, b, hip_stream, nullptr, 0);
+}
+
+flp_status flp_lora_apply_gated(flp_pool* p, const flp_lora_batch* b, void* out, int64_t ld_out, void* hip_stream) {
+  if (!out || ((uintptr_t)out & 15)) {
+    flp_set_error("flp_lora_apply_gated: out is null or misaligned");
+    return FLP_EINVAL;
+  }
+  return lora_apply_impl(p, b, hip_stream, out, ld_out);
+}
+
+namespace {
+// gated_out != nullptr: two projections (gate, up) whose results are not stored; gated_out = silu(y0) * y1
+flp_status lora_apply_impl(flp_pool* p, const flp_lora_batch* b, void* hip_stream, void* gated_out, int64_t ld_gated) {
   if (!p || !b) {
     flp_set_error("flp_lora_apply_paged: null pool or batch");
     return FLP_EINVAL;
@@ -333,6 +351,12 @@ extern "C" flp_status flp_lora_apply_paged(flp_pool* p, const flp_lora_batch* b,
   for (int q = 0; q < b->n_proj; ++q)
     fused = fused && b->proj[q].w_base &&
             flp_gemm_is_large(p->cfg.dtype, b->n_tokens, b->proj[q].d_out, b->d_in, b->ld_x);
+  if (gated_out) {
+    const bool ok = fused && b->n_proj == 2 && b->proj[0].d_out == b->proj[1].d_out && b->proj[0].w_base_layout == 1 &&
+                    b->proj[1].w_base_layout == 1 && ld_gated >= b->proj[0].d_out && ld_gated % epl == 0 &&
+                    flp_gemm_gated_fits(p->cfg.dtype, b->n_tokens, b->proj[0].d_out, b->d_in, b->ld_x);
+    if (!ok) return FLP_ENOTSUP;                // nothing launched: the caller takes the separate products
+  }
   size_t wt_bytes = 0;                         // transposed copy of the widest dense base matrix
   if (p->elem_bytes == 2)
     for (int q = 0; q < b->n_proj; ++q)
@@ -388,7 +412,7 @@ extern "C" flp_status flp_lora_apply_paged(flp_pool* p, const flp_lora_batch* b,
     c.shrink_only = 1;
     FLP_TRY(flp_launch_lora_mfma(p->cfg.dtype, a, c, stream));
     const int nt = (b->max_rank + 15) / 16 <= 2 ? (b->max_rank + 15) / 16 : 4;
-    for (int q = 0; q < b->n_proj; ++q) {
+    auto branch = [&](int q) {
       FlpGemmLora lp{};
       lp.token_adapter = a.token_adapter;
       lp.rank = a.rank;
@@ -412,6 +436,15 @@ extern "C" flp_status flp_lora_apply_paged(flp_pool* p, const flp_lora_batch* b,
       lp.seg_adapter = a.seg_adapter;
       lp.seg_start = a.seg_start;
       lp.tile_start = a.tile_start;
+      return lp;
+    };
+    if (gated_out) {
+      const FlpGemmLora lg = branch(0), lu = branch(1);
+      return flp_launch_gated_gemm(p->cfg.dtype, b->x, b->ld_x, b->proj[0].w_base, b->proj[1].w_base, gated_out, ld_gated,
+                                   b->n_tokens, b->proj[0].d_out, b->d_in, stream, &lg, &lu);
+    }
+    for (int q = 0; q < b->n_proj; ++q) {
+      const FlpGemmLora lp = branch(q);
       FLP_TRY(flp_launch_base_gemm(p->cfg.dtype, b->x, b->ld_x, b->proj[q].w_base, b->proj[q].w_base_layout,
                                    b->proj[q].y, b->proj[q].ld_y, b->n_tokens, b->proj[q].d_out, b->d_in, wt, nullptr,
                                    nullptr, 0, stream, &lp));
@@ -440,3 +473,4 @@ extern "C" flp_status flp_lora_apply_paged(flp_pool* p, const flp_lora_batch* b,
                                   16 * c.mt, a.tile_start, c.group_tokens, a.group_start, stream));
   return flp_launch_lora_mfma(p->cfg.dtype, a, c, stream);
 }
+}  // namespace

@@ -196,6 +196,14 @@ bool flp_gemm_is_large(int dtype, int M, int N, int K, int64_t ld_x);
 // silu(x . Wg^T) * (x . Wu^T) in one pass (16-bit types, weights [N, K]); FLP_ENOTSUP, nothing launched, for shapes
 // that the large-batch kernel does not take
 flp_status flp_launch_gated_gemm(int dtype, const void* x, int64_t ld_x, const void* w_gate, const void* w_up,
-                                 void* out, int64_t ld_out, int M, int N, int K, hipStream_t stream);
+                                 void* out, int64_t ld_out, int M, int N, int K, hipStream_t stream,
+                                 const FlpGemmLora* lora_gate = nullptr, const FlpGemmLora* lora_up = nullptr);
+// true when flp_launch_gated_gemm takes this shape
+bool flp_gemm_gated_fits(int dtype, int M, int N, int K, int64_t ld_x);
+// flp_lora_apply_paged for exactly two projections with dense bases stored [d_out, d_in] and equal widths (gate and
+// up of an MLP), whose results are not stored: out = silu(y0) * y1 in one pass of the large-batch GEMM, each product
+// with its LoRA branch added before it is rounded.  FLP_ENOTSUP, nothing launched, when the batch is not one that
+// this path takes; the caller then runs flp_lora_apply_paged and the element-wise step.
+flp_status flp_lora_apply_gated(flp_pool* pool, const flp_lora_batch* batch, void* out, int64_t ld_out, void* hip_stream);
 // bytes of split-K scratch worth offering for an [M, N] product (0 for large batches, which are not split)
 inline size_t flp_gemm_splitk_bytes(int M, int N) { return M <= 1024 ? (size_t)8 * M * N * 4 : 0; }

@@ -236,7 +236,8 @@ __global__ __launch_bounds__(256, 1) void gemm_nt256_kernel(const uint16_t* __re
                                                             const uint16_t* __restrict__ wt,
                                                             const uint16_t* __restrict__ wt2, uint16_t* __restrict__ y,
                                                             int64_t ld_y, float* __restrict__ y32, int M, int N, int K,
-                                                            int tiles_n, int tiles_m, int groups_n, FlpGemmLora lp) {
+                                                            int tiles_n, int tiles_m, int groups_n, FlpGemmLora lpa,
+                                                            FlpGemmLora lp2) {
   constexpr int GTN = GATED ? GT / 2 : GT;              // output features per tile
   typedef typename G::vec vec;
   extern __shared__ __attribute__((aligned(1024))) uint8_t smem[];
@@ -352,50 +353,11 @@ __global__ __launch_bounds__(256, 1) void gemm_nt256_kernel(const uint16_t* __re
   }
   __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));               // the look-ahead loads must land before the LDS is released
 
-  if constexpr (GATED) {
-    // the up waves' 256 accumulator values per lane, [token half][value][lane] in the 128 KiB the stages leave
-    float* xch = reinterpret_cast<float*>(smem) + (wj * 256) * 64 + lane;
-    __syncthreads();                                       // everybody's loads have landed, nobody reads fragments any more
-    if (wi == 1) {
-#pragma unroll
-      for (int i = 0; i < 4; ++i)
-#pragma unroll
-        for (int j = 0; j < 4; ++j)
-#pragma unroll
-          for (int e = 0; e < 16; ++e) xch[((i * 4 + j) * 16 + e) * 64] = acc[i][j][e];
-    }
-    __syncthreads();
-    if (wi == 1) return;
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      const int m = m0 + 128 * wj + 32 * j + acol;
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const int n = n0 + 32 * i + 16 * hf;
-        uint16_t o[16];
-#pragma unroll
-        for (int e = 0; e < 16; ++e) {
-          const float g = G::in(G::out(acc[i][j][e])), u = G::in(G::out(xch[((i * 4 + j) * 16 + e) * 64]));
-          o[e] = G::out(g / (1.0f + expf(-g)) * u);
-        }
-        if (m >= M || n >= N) continue;
-        uint16_t* yp = y + (int64_t)m * ld_y + n;
-        if (n + 16 <= N) {
-          u32x4 raw[2];
-          __builtin_memcpy(raw, o, 32);
-          reinterpret_cast<u32x4*>(yp)[0] = raw[0];
-          reinterpret_cast<u32x4*>(yp)[1] = raw[1];
-        } else {
-          for (int e = 0; e < 16; ++e)
-            if (n + e < N) yp[e] = o[e];
-        }
-      }
-    }
-    return;
-  }
-
   if constexpr (LORA) {
     typedef typename G::elem elem;
+    // a gated tile's up waves add the up projection's branch (lp2), everybody else the projection's own (lpa)
+    const FlpGemmLora& lp = GATED && wi == 1 ? lp2 : lpa;
+    const int fbase = GATED ? n0 : n0 + 128 * wi;         // the wave's first feature
     const uint16_t* __restrict__ pool = reinterpret_cast<const uint16_t*>(lp.pool);
     const int n_seg = *lp.n_seg;
     const int rpb = (int)(lp.block_elems / N);
@@ -438,7 +400,7 @@ __global__ __launch_bounds__(256, 1) void gemm_nt256_kernel(const uint16_t* __re
           vec af[4];
 #pragma unroll
           for (int i = 0; i < 4; ++i) {
-            const int f = n0 + 128 * wi + 32 * i + acol;
+            const int f = fbase + 32 * i + acol;
             const int fc = f < N ? f : N - 1;
             uint16_t g8[8];
 #pragma unroll
@@ -485,6 +447,48 @@ __global__ __launch_bounds__(256, 1) void gemm_nt256_kernel(const uint16_t* __re
 #pragma unroll
       for (int j = 0; j < 4; ++j) adj[j] = adj[j] == ad ? -1 : adj[j];
     }
+  }
+
+  if constexpr (GATED) {
+    // the up waves' 256 accumulator values per lane, [token half][value][lane] in the 128 KiB the stages leave
+    float* xch = reinterpret_cast<float*>(smem) + (wj * 256) * 64 + lane;
+    __syncthreads();                                       // everybody's loads have landed, nobody reads fragments any more
+    if (wi == 1) {
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+          for (int e = 0; e < 16; ++e) xch[((i * 4 + j) * 16 + e) * 64] = acc[i][j][e];
+    }
+    __syncthreads();
+    if (wi == 1) return;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int m = m0 + 128 * wj + 32 * j + acol;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int n = n0 + 32 * i + 16 * hf;
+        uint16_t o[16];
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+          const float g = G::in(G::out(acc[i][j][e])), u = G::in(G::out(xch[((i * 4 + j) * 16 + e) * 64]));
+          o[e] = G::out(g / (1.0f + expf(-g)) * u);
+        }
+        if (m >= M || n >= N) continue;
+        uint16_t* yp = y + (int64_t)m * ld_y + n;
+        if (n + 16 <= N) {
+          u32x4 raw[2];
+          __builtin_memcpy(raw, o, 32);
+          reinterpret_cast<u32x4*>(yp)[0] = raw[0];
+          reinterpret_cast<u32x4*>(yp)[1] = raw[1];
+        } else {
+          for (int e = 0; e < 16; ++e)
+            if (n + e < N) yp[e] = o[e];
+        }
+      }
+    }
+    return;
   }
 
   // lane (token acol of tile j, half hf) holds columns 16*hf .. 16*hf+15 of feature tile i
@@ -553,9 +557,10 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(const float* __restrict__
 }
 
 flp_status gemm256_attrs() {
-  const void* fns[6] = {(const void*)gemm_nt256_kernel<GF16, false, false>, (const void*)gemm_nt256_kernel<GBF16, false, false>,
+  const void* fns[8] = {(const void*)gemm_nt256_kernel<GF16, false, false>, (const void*)gemm_nt256_kernel<GBF16, false, false>,
                         (const void*)gemm_nt256_kernel<GF16, true, false>, (const void*)gemm_nt256_kernel<GBF16, true, false>,
-                        (const void*)gemm_nt256_kernel<GF16, false, true>, (const void*)gemm_nt256_kernel<GBF16, false, true>};
+                        (const void*)gemm_nt256_kernel<GF16, false, true>, (const void*)gemm_nt256_kernel<GBF16, false, true>,
+                        (const void*)gemm_nt256_kernel<GF16, true, true>, (const void*)gemm_nt256_kernel<GBF16, true, true>};
   for (const void* f : fns)
     FLP_TRY_HIP(hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, kGStages * kGStage));
   return FLP_OK;
@@ -575,10 +580,12 @@ bool gemm256_fits(int64_t M, int64_t n_rows_w, int64_t K, int64_t ld_x) {
 // take (small batches, few tiles, offsets beyond 32 bits): the caller then runs the two products and the
 // element-wise step.
 flp_status flp_launch_gated_gemm(int dtype, const void* x, int64_t ld_x, const void* w_gate, const void* w_up,
-                                 void* out, int64_t ld_out, int M, int N, int K, hipStream_t stream) {
+                                 void* out, int64_t ld_out, int M, int N, int K, hipStream_t stream,
+                                 const FlpGemmLora* lora_gate, const FlpGemmLora* lora_up) {
   if (dtype != FLP_F16 && dtype != FLP_BF16) return FLP_ENOTSUP;
   const int tiles_n = (N + GT / 2 - 1) / (GT / 2), tiles_m = (M + GT - 1) / GT;
   if (M <= 0 || N < 128 || K <= 0 || !gemm256_fits(M, N, K, ld_x) || (int64_t)tiles_n * tiles_m < 96) return FLP_ENOTSUP;
+  if ((lora_gate != nullptr) != (lora_up != nullptr)) return FLP_ENOTSUP;
   static bool attr_set = false;
   if (!attr_set) {
     FLP_TRY(gemm256_attrs());
@@ -587,16 +594,28 @@ flp_status flp_launch_gated_gemm(int dtype, const void* x, int64_t ld_x, const v
   const int groups_n = (tiles_n + 3) / 4, groups_m = (tiles_m + 7) / 8;
   const int n_groups = (groups_n * groups_m + 7) / 8 * 8;
   dim3 grid((unsigned)(n_groups * 32));
-  if (dtype == FLP_F16)
-    hipLaunchKernelGGL((gemm_nt256_kernel<GF16, true, false>), grid, dim3(256), kGStages * kGStage, stream,
-                       (const uint16_t*)x, ld_x, (const uint16_t*)w_gate, (const uint16_t*)w_up, (uint16_t*)out, ld_out,
-                       (float*)nullptr, M, N, K, tiles_n, tiles_m, groups_n, FlpGemmLora{});
+  const uint16_t *xs = (const uint16_t*)x, *wg = (const uint16_t*)w_gate, *wu = (const uint16_t*)w_up;
+  float* no32 = nullptr;
+  const size_t lds = kGStages * kGStage;
+  if (lora_gate && dtype == FLP_F16)
+    hipLaunchKernelGGL((gemm_nt256_kernel<GF16, true, true>), grid, dim3(256), lds, stream, xs, ld_x, wg, wu, (uint16_t*)out,
+                       ld_out, no32, M, N, K, tiles_n, tiles_m, groups_n, *lora_gate, *lora_up);
+  else if (lora_gate)
+    hipLaunchKernelGGL((gemm_nt256_kernel<GBF16, true, true>), grid, dim3(256), lds, stream, xs, ld_x, wg, wu, (uint16_t*)out,
+                       ld_out, no32, M, N, K, tiles_n, tiles_m, groups_n, *lora_gate, *lora_up);
+  else if (dtype == FLP_F16)
+    hipLaunchKernelGGL((gemm_nt256_kernel<GF16, true, false>), grid, dim3(256), lds, stream, xs, ld_x, wg, wu, (uint16_t*)out,
+                       ld_out, no32, M, N, K, tiles_n, tiles_m, groups_n, FlpGemmLora{}, FlpGemmLora{});
   else
-    hipLaunchKernelGGL((gemm_nt256_kernel<GBF16, true, false>), grid, dim3(256), kGStages * kGStage, stream,
-                       (const uint16_t*)x, ld_x, (const uint16_t*)w_gate, (const uint16_t*)w_up, (uint16_t*)out, ld_out,
-                       (float*)nullptr, M, N, K, tiles_n, tiles_m, groups_n, FlpGemmLora{});
+    hipLaunchKernelGGL((gemm_nt256_kernel<GBF16, true, false>), grid, dim3(256), lds, stream, xs, ld_x, wg, wu,
+                       (uint16_t*)out, ld_out, no32, M, N, K, tiles_n, tiles_m, groups_n, FlpGemmLora{}, FlpGemmLora{});
   FLP_TRY_HIP(hipGetLastError());
   return FLP_OK;
+}
+
+bool flp_gemm_gated_fits(int dtype, int M, int N, int K, int64_t ld_x) {
+  return (dtype == FLP_F16 || dtype == FLP_BF16) && M > 0 && N >= 128 && K > 0 && gemm256_fits(M, N, K, ld_x) &&
+         (int64_t)((N + GT / 2 - 1) / (GT / 2)) * ((M + GT - 1) / GT) >= 96;
 }
 
 bool flp_gemm_is_large(int dtype, int M, int N, int K, int64_t ld_x) {
@@ -646,16 +665,16 @@ flp_status flp_launch_base_gemm(int dtype, const void* x, int64_t ld_x, const vo
     const uint16_t* none = nullptr;
     if (lora && dtype == FLP_F16)
       hipLaunchKernelGGL((gemm_nt256_kernel<GF16, false, true>), grid256, dim3(256), kGStages * kGStage, stream, xs, ld_x,
-                         ws, none, (uint16_t*)y, ld_y, y32, M, N, K, tiles_n, tiles_m, groups_n, *lora);
+                         ws, none, (uint16_t*)y, ld_y, y32, M, N, K, tiles_n, tiles_m, groups_n, *lora, FlpGemmLora{});
     else if (lora)
       hipLaunchKernelGGL((gemm_nt256_kernel<GBF16, false, true>), grid256, dim3(256), kGStages * kGStage, stream, xs, ld_x,
-                         ws, none, (uint16_t*)y, ld_y, y32, M, N, K, tiles_n, tiles_m, groups_n, *lora);
+                         ws, none, (uint16_t*)y, ld_y, y32, M, N, K, tiles_n, tiles_m, groups_n, *lora, FlpGemmLora{});
     else if (dtype == FLP_F16)
       hipLaunchKernelGGL((gemm_nt256_kernel<GF16, false, false>), grid256, dim3(256), kGStages * kGStage, stream, xs, ld_x,
-                         ws, none, (uint16_t*)y, ld_y, y32, M, N, K, tiles_n, tiles_m, groups_n, FlpGemmLora{});
+                         ws, none, (uint16_t*)y, ld_y, y32, M, N, K, tiles_n, tiles_m, groups_n, FlpGemmLora{}, FlpGemmLora{});
     else
       hipLaunchKernelGGL((gemm_nt256_kernel<GBF16, false, false>), grid256, dim3(256), kGStages * kGStage, stream, xs,
-                         ld_x, ws, none, (uint16_t*)y, ld_y, y32, M, N, K, tiles_n, tiles_m, groups_n, FlpGemmLora{});
+                         ld_x, ws, none, (uint16_t*)y, ld_y, y32, M, N, K, tiles_n, tiles_m, groups_n, FlpGemmLora{}, FlpGemmLora{});
     FLP_TRY_HIP(hipGetLastError());
     return FLP_OK;
   }

@@ -306,7 +306,7 @@ extern "C" flp_status fll_layer_forward(flp_pool* p, const fll_layer_config* c, 
 
   // base GEMM + LoRA branch of up to three projections that share their input
   auto project = [&](const void* x, int d_in, int n_proj, const int* which, void* const* ys, const int* d_outs,
-                     const void* const* ws) -> flp_status {
+                     const void* const* ws, void* gated_out = nullptr) -> flp_status {
     flp_lora_batch lb{};
     lb.n_tokens = T;
     lb.d_in = d_in;
@@ -358,6 +358,7 @@ extern "C" flp_status fll_layer_forward(flp_pool* p, const fll_layer_config* c, 
     }
     if (n_lora == 0) return FLP_OK;
     lb.n_proj = n_lora;
+    if (gated_out) return flp_lora_apply_gated(p, &lb, gated_out, d_outs[0], hip_stream);
     return flp_lora_apply_paged(p, &lb, hip_stream);
   };
 
@@ -398,13 +399,19 @@ extern "C" flp_status fll_layer_forward(flp_pool* p, const fll_layer_config* c, 
       const fll_lora_place& pl = b->lora[i];
       return !pl.a_tab_off && !pl.a_row_base && !pl.b_tab_off && !pl.b_row_base;
     };
+    const auto full_lora = [&](int i) {
+      const fll_lora_place& pl = b->lora[i];
+      return pl.a_tab_off && pl.a_row_base && pl.b_tab_off && pl.b_row_base;
+    };
+    const int which[2] = {4, 5}, d_outs[2] = {M, M};
+    void* const ys[2] = {gate, up};
+    const void* const ws[2] = {w->w_gate, w->w_up};
     flp_status fused = FLP_ENOTSUP;
     if (no_lora(4) && no_lora(5))
       fused = flp_launch_gated_gemm(dtype, n, H, w->w_gate, w->w_up, gate, M, T, M, H, (hipStream_t)hip_stream);
+    else if (full_lora(4) && full_lora(5))          // both with a LoRA branch: the branches are added inside the same pass
+      fused = project(n, H, 2, which, ys, d_outs, ws, gate);
     if (fused == FLP_ENOTSUP) {
-      const int which[2] = {4, 5}, d_outs[2] = {M, M};
-      void* const ys[2] = {gate, up};
-      const void* const ws[2] = {w->w_gate, w->w_up};
       FLP_TRY(project(n, H, 2, which, ys, d_outs, ws));
       FLP_TRY(fll_silu_mul(dtype, gate, M, up, M, gate, M, T, M, hip_stream));
     } else if (fused != FLP_OK) {
