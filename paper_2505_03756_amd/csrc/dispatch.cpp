@@ -378,7 +378,8 @@ flp_status lora_apply_impl(flp_pool* p, const flp_lora_batch* b, void* hip_strea
   const size_t v_bytes = (v_elems * 4 + 255) & ~(size_t)255;
   const size_t seg_bytes = ((size_t)(4 * b->n_adapters + 5) * 4 + 255) & ~(size_t)255;
   const size_t perm_bytes = (T * 4 + 255) & ~(size_t)255;
-  const size_t inv_bytes = fused ? perm_bytes : 0;      // token -> position in segment order
+  // token -> position in segment order, adapter -> first row of its tokens in the shrink output
+  const size_t inv_bytes = fused ? perm_bytes + (((size_t)b->n_adapters * 4 + 255) & ~(size_t)255) : 0;
   void* ws = nullptr;
   FLP_TRY(flp_workspace(p, v_bytes + seg_bytes + perm_bytes + wt_bytes + base_total + splitk_bytes + inv_bytes, &ws));
   FlpLoraArgs a{};
@@ -407,8 +408,9 @@ flp_status lora_apply_impl(flp_pool* p, const flp_lora_batch* b, void* hip_strea
   if (fused) {
     int32_t* inv_perm = (int32_t*)(w + v_bytes + seg_bytes + perm_bytes + wt_bytes + base_total + splitk_bytes);
     uint8_t* wt = w + v_bytes + seg_bytes + perm_bytes;
+    int32_t* vrow_base = (int32_t*)((uint8_t*)inv_perm + perm_bytes);
     FLP_TRY(flp_launch_lora_segment(a.T, a.token_adapter, a.n_adapters, a.n_seg, a.seg_adapter, a.seg_start, a.perm,
-                                    16 * c.mt, a.tile_start, c.group_tokens, a.group_start, stream, inv_perm));
+                                    16 * c.mt, a.tile_start, c.group_tokens, a.group_start, stream, inv_perm, vrow_base));
     c.shrink_only = 1;
     FLP_TRY(flp_launch_lora_mfma(p->cfg.dtype, a, c, stream));
     const int nt = (b->max_rank + 15) / 16 <= 2 ? (b->max_rank + 15) / 16 : 4;
@@ -430,12 +432,8 @@ flp_status lora_apply_impl(flp_pool* p, const flp_lora_batch* b, void* hip_strea
       lp.rp = 16 * nt;
       lp.n_adapters = b->n_adapters;
       lp.max_rank = b->max_rank < 16 * nt ? b->max_rank : 16 * nt;
-      lp.tm = 16 * c.mt;
       lp.inv_perm = inv_perm;
-      lp.n_seg = a.n_seg;
-      lp.seg_adapter = a.seg_adapter;
-      lp.seg_start = a.seg_start;
-      lp.tile_start = a.tile_start;
+      lp.vrow_base = vrow_base;
       return lp;
     };
     if (gated_out) {

@@ -160,8 +160,8 @@ struct FlpLoraMfma {
 
 // What the large-batch dense product needs to add one projection's LoRA branch to its accumulators before it
 // rounds (the expand step as an epilogue: y = round(x . W + s (x A^T) B), no fp32 copy of the product, no second
-// pass over y).  v is the shrink step's output, rows in segment order: token t of segment s sits in row
-// tile_start[s] * tm + inv_perm[t] - seg_start[s].
+// pass over y).  v is the shrink step's output, rows in segment order: token t of adapter a sits in row
+// vrow_base[a] + inv_perm[t] (both written by the segmentation kernel).
 struct FlpGemmLora {
   const int32_t* token_adapter;
   const int32_t* rank;
@@ -173,18 +173,15 @@ struct FlpGemmLora {
   int64_t block_elems;
   const float* v;              // [k_splits][v_rows][n_proj][rp] fp32
   int32_t v_rows, k_splits, n_proj, p, rp;
-  int32_t n_adapters, max_rank, tm;
+  int32_t n_adapters, max_rank;
   const int32_t* inv_perm;     // [T] token -> position in segment order
-  const int32_t* n_seg;
-  const int32_t* seg_adapter;  // ascending adapter ids of the non-empty segments
-  const int32_t* seg_start;
-  const int32_t* tile_start;
+  const int32_t* vrow_base;    // [n_adapters]
 };
 
 flp_status flp_launch_lora_segment(int32_t T, const int32_t* token_adapter, int32_t n_adapters, int32_t* n_seg,
                                    int32_t* seg_adapter, int32_t* seg_start, int32_t* perm, int32_t tm,
                                    int32_t* tile_start, int32_t tg, int32_t* group_start, hipStream_t stream,
-                                   int32_t* inv_perm = nullptr);
+                                   int32_t* inv_perm = nullptr, int32_t* vrow_base = nullptr);
 flp_status flp_launch_lora_mfma(int dtype, const FlpLoraArgs& a, const FlpLoraMfma& c, hipStream_t stream);
 flp_status flp_launch_lora_simple(int dtype, const FlpLoraArgs& a, hipStream_t stream);
 flp_status flp_launch_base_gemm(int dtype, const void* x, int64_t ld_x, const void* w, int w_layout, void* y,

@@ -359,7 +359,6 @@ __global__ __launch_bounds__(256, 1) void gemm_nt256_kernel(const uint16_t* __re
     const FlpGemmLora& lp = GATED && wi == 1 ? lp2 : lpa;
     const int fbase = GATED ? n0 : n0 + 128 * wi;         // the wave's first feature
     const uint16_t* __restrict__ pool = reinterpret_cast<const uint16_t*>(lp.pool);
-    const int n_seg = *lp.n_seg;
     const int rpb = (int)(lp.block_elems / N);
     int adj[4], posj[4];                                  // adapter and segment-order position of the lane's four tokens
 #pragma unroll
@@ -380,12 +379,7 @@ __global__ __launch_bounds__(256, 1) void gemm_nt256_kernel(const uint16_t* __re
       const int r = lp.rank[ad] < lp.max_rank ? lp.rank[ad] : lp.max_rank;
       if (r > 0) {
         const float sc = lp.scale[ad];
-        int lo = 0, hi = n_seg;                               // the adapter's segment: seg_adapter is ascending
-        while (hi - lo > 1) {
-          const int mid = (lo + hi) >> 1;
-          if (lp.seg_adapter[mid] <= ad) lo = mid; else hi = mid;
-        }
-        const int64_t vrow0 = (int64_t)lp.tile_start[lo] * lp.tm - lp.seg_start[lo];
+        const int64_t vrow0 = lp.vrow_base[ad];
         const int32_t* __restrict__ tab = lp.tables + lp.b_tab_off[ad];
         const int brow0 = lp.b_row_base[ad];
         for (int nt = 0; 16 * nt < r; ++nt) {

@@ -25,7 +25,8 @@ __global__ __launch_bounds__(1024) void lora_segment_kernel(int32_t T, const int
                                                             int32_t* __restrict__ perm, int32_t tm,
                                                             int32_t* __restrict__ tile_start, int32_t tg,
                                                             int32_t* __restrict__ group_start,
-                                                            int32_t* __restrict__ inv_perm) {
+                                                            int32_t* __restrict__ inv_perm,
+                                                            int32_t* __restrict__ vrow_base) {
   extern __shared__ int32_t sm[];
   int32_t* whist = sm;                         // [kSegWaves][n_ad]: counts, then running cursors
   int32_t* tot = sm + kSegWaves * n_ad;        // [n_ad] tokens per adapter
@@ -141,6 +142,9 @@ __global__ __launch_bounds__(1024) void lora_segment_kernel(int32_t T, const int
       int a = tid * per + k;
       if (a < n_ad) {
         seg_off[a] = pos;
+        // row of the shrink output that holds the adapter's first token, minus that token's position: a token at
+        // position pos sits in row vrow_base[a] + pos
+        if (vrow_base) vrow_base[a] = tl * tm - pos;
         if (tot[a] > 0) {
           seg_adapter[seg] = a;
           seg_start[seg] = pos;
@@ -465,7 +469,7 @@ __global__ __launch_bounds__(256) void lora_expand_rows_kernel(FlpLoraArgs a) {
 flp_status flp_launch_lora_segment(int32_t T, const int32_t* token_adapter, int32_t n_adapters, int32_t* n_seg,
                                    int32_t* seg_adapter, int32_t* seg_start, int32_t* perm, int32_t tm,
                                    int32_t* tile_start, int32_t tg, int32_t* group_start, hipStream_t stream,
-                                   int32_t* inv_perm) {
+                                   int32_t* inv_perm, int32_t* vrow_base) {
   const size_t smem = ((size_t)(kSegWaves + 2) * (size_t)(n_adapters > 0 ? n_adapters : 1) + 4 * kSegWaves + 4) * 4;
   static bool attr_set = false;
   if (!attr_set) {
@@ -474,7 +478,7 @@ flp_status flp_launch_lora_segment(int32_t T, const int32_t* token_adapter, int3
     attr_set = true;
   }
   hipLaunchKernelGGL(lora_segment_kernel, dim3(1), dim3(1024), smem, stream, T, token_adapter, n_adapters, n_seg,
-                     seg_adapter, seg_start, perm, tm, tile_start, tg, group_start, inv_perm);
+                     seg_adapter, seg_start, perm, tm, tile_start, tg, group_start, inv_perm, vrow_base);
   FLP_TRY_HIP(hipGetLastError());
   return FLP_OK;
 }
