@@ -164,6 +164,10 @@ def main():
             self.g, self.step = g, g.step
             self.T = g.step.n_tokens
             self.ys = {n: g.acts["base_" + n].clone() for n in cfg.projections}
+            # projections without a LoRA branch (the tiny config has q and v only): their base terms as they are
+            for n, key in (("q", "q"), ("k", "k_new"), ("v", "v_new")):
+                if n not in self.ys:
+                    self.ys[n] = g.acts[key]
             self.attn_out = torch.zeros_like(self.ys["q"])
             self.n_ad, self.max_rank = len(g.step.rank), int(max(1, g.step.rank.max()))
 
@@ -190,6 +194,8 @@ def main():
 
         def lora_o(self, st):
             g = self.g
+            if "o" not in cfg.projections:
+                return
             g.pool.lora_apply_paged(self.attn_out, g.token_adapter, g.rank, g.scale, g.lora_tables, [self.pj("o")],
                                     n_tokens=self.T, d_in=qd, n_adapters=self.n_ad, max_rank=self.max_rank, stream=st)
 
@@ -279,7 +285,8 @@ def main():
         "lora_qkv": {"bound": "hbm", "bytes": lora_bytes(names_qkv, cfg.hidden), "flops": lora_flops(names_qkv, cfg.hidden)},
         "kv_append": {"bound": "hbm", "bytes": append_bytes},
         "attention": {"bound": "hbm", "bytes": attn_bytes, "flops": attn_flops},
-        "lora_o": {"bound": "hbm", "bytes": lora_bytes(["o"], qd), "flops": lora_flops(["o"], qd)},
+        "lora_o": {"bound": "hbm", "bytes": lora_bytes(["o"], qd), "flops": lora_flops(["o"], qd)}
+        if "o" in cfg.projections else {"bound": "hbm", "bytes": 0.0, "flops": 0.0},
     }
     for name, k in kernels.items():
         ms = stage_ms[name]
