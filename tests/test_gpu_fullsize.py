@@ -114,3 +114,35 @@ def test_34b_gqa_shapes_in_full_size_pool():
     """Config 4 shapes (hidden 8192, 64 query / 8 kv heads, rank 64, prefixes up to 16384, 75 % decode) on a
     seeded subsample of 64 sequences, in a device tier of 3 000 000 x 64 KiB (197 GB)."""
     _run_case(wl.config("34b_gqa").scaled(n_seqs=64, n_dev_blocks=3000000, n_host_blocks=8192), n_sample_tokens=36)
+
+
+def test_7b_prefill_dense_base_full_size():
+    """The q, k, v call of the headline batch with the dense base computed by the library (w_base given): at this
+    size the products take the large-batch GEMM and the LoRA branch is added inside it.  Sampled tokens (a random
+    sample and both ends of every sequence) against the oracle."""
+    import torch
+    cfg = wl.config("7b_prefill")
+    step = wl.make_step(cfg)
+    T = step.n_tokens
+    rng = np.random.default_rng(4321)
+    rtol, atol = TOL[cfg.dtype]
+    gp = SparseGpuPool(step)
+    g = GpuStep(step, gpool=gp)
+    pool_c, kv_c, lt_c = compact_step(step)
+    g.pool.swap_in(step.swap_in_host, step.swap_in_dev)
+    torch.cuda.synchronize()
+    names = ["q", "k", "v"]
+    W = {n: wl.quantize((rng.standard_normal((cfg.hidden, step.proj[n].d_out)) / np.sqrt(cfg.hidden)).astype(np.float32),
+                        cfg.dtype) for n in names}
+    got = g.lora(names, w_base={n: to_dev(W[n]) for n in names})
+    sel = np.unique(np.concatenate([rng.choice(T, size=24, replace=False), step.cu_new[:-1][::4],
+                                    step.cu_new[1:][::4] - 1, [T - 1]])).astype(np.int32)
+    for n in names:
+        pr = step.proj[n]
+        want = oracle.lora_apply(pool_c, cfg.dtype, step.acts["x"], step.token_adapter, step.rank, step.scale,
+                                 pr.a_tab_off, pr.a_row_base, pr.b_tab_off, pr.b_row_base, lt_c, pr.d_out,
+                                 w_base=W[n], sel=sel)
+        ok, worst, nbad = close(wl.dequantize(got[n][sel], cfg.dtype), want, rtol, atol)
+        assert ok, "%s: max err %g (%d bad)" % (n, worst, nbad)
+        assert np.abs(want).max() > 1.0
+    gp.pool.close()
