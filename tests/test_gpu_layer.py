@@ -252,3 +252,56 @@ def test_two_layer_stack_with_per_layer_pools():
     a, b = lo.load(img1, cfg.dtype), lo.load(pools_o[1][fresh], cfg.dtype)
     m = np.isfinite(a) & np.isfinite(b)
     assert (np.isfinite(a) == np.isfinite(b)).all() and np.abs(a[m] - b[m]).max() <= 16 * ULP[cfg.dtype] * max(1.0, np.abs(b[m]).max())
+
+
+def test_7b_layer_full_size_against_the_oracle_on_two_sequences():
+    """One decoder layer at the benchmark's size (7B shapes: hidden 4096, 32 heads, MLP 11008, LoRA rank 16 on q, k,
+    v, o; the 18 953-token batch, the 4 GiB pool).  A token's output depends only on its own sequence, so the oracle
+    runs the layer on two of the 64 sequences and their rows of the GPU's full-batch result are compared."""
+    import types
+    import torch
+    from paper_2505_03756_amd.harness import SparseGpuPool, compact_step
+    cfg = wl.config("7b_prefill")
+    step = wl.make_step(cfg)
+    T = step.n_tokens
+    gp = SparseGpuPool(step)
+    g = GpuStep(step, gpool=gp)
+    pool_c, kv_c, lt_c = compact_step(step)
+    g.pool.swap_in(step.swap_in_host, step.swap_in_dev)
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(11)
+    mlp = 11008
+    dims = {"q": (4096, 4096), "k": (4096, 4096), "v": (4096, 4096), "o": (4096, 4096), "gate": (mlp, 4096),
+            "up": (mlp, 4096), "down": (4096, mlp)}
+    W = {"in_norm": rng.normal(1, 0.1, 4096), "post_norm": rng.normal(1, 0.1, 4096)}
+    for n, (d_out, d_in) in dims.items():
+        W[n] = rng.standard_normal((d_out, d_in), dtype=np.float32) / np.float32(math.sqrt(d_in))
+    W = {k: lo.round_store(v, cfg.dtype)[0] for k, v in W.items()}
+    h0_st, _ = lo.round_store(rng.standard_normal((T, 4096), dtype=np.float32), cfg.dtype)
+    pos = np.concatenate([step.prefix_len[i] + np.arange(step.cu_new[i + 1] - step.cu_new[i])
+                          for i in range(cfg.n_seqs)]).astype(np.int32)
+    layer = fllayer.Layer(g.pool, 4096, cfg.n_q_heads, mlp, {k: to_dev(v) for k, v in W.items()})
+    batch = fllayer.Batch(step.cu_new, step.prefix_len, to_dev(pos), g.kv_tables, g.token_adapter, g.rank, g.scale,
+                          g.lora_tables, g.proj, n_adapters=len(step.rank), max_rank=int(step.rank.max()),
+                          max_blocks_per_seq=step.kv_tables.shape[1])
+    nbytes = layer.scratch_bytes(T)
+    scratch = torch.zeros(nbytes + 256, dtype=torch.uint8, device="cuda")
+    h = to_dev(h0_st)
+    layer.forward(batch, h, (scratch.data_ptr() + 255) & ~255, nbytes)
+    torch.cuda.synchronize()
+    got_all = to_np(h, h0_st.dtype)
+
+    # the oracle on the longest-context sequence and the last one (whose rows end the batch's last, partly filled tile)
+    seqs = sorted({int(np.argmax(step.prefix_len + np.diff(step.cu_new))), cfg.n_seqs - 1})
+    rows = np.concatenate([np.arange(step.cu_new[i], step.cu_new[i + 1]) for i in seqs])
+    lens = np.array([step.cu_new[i + 1] - step.cu_new[i] for i in seqs])
+    sub = types.SimpleNamespace(n_tokens=int(lens.sum()), proj={n: step.proj[n] for n in cfg.projections},
+                                token_adapter=step.token_adapter[rows], rank=step.rank, scale=step.scale,
+                                lora_tables=lt_c, cu_new=np.concatenate([[0], np.cumsum(lens)]).astype(np.int32),
+                                prefix_len=step.prefix_len[seqs], kv_tables=np.ascontiguousarray(kv_c[seqs]))
+    want_st, _ = lo.layer_forward(cfg, sub, pool_c, W, h0_st[rows], pos[rows])
+    got, want = lo.load(got_all[rows], cfg.dtype), lo.load(want_st, cfg.dtype)
+    ok, worst, nbad = close(got, want, 8 * ULP[cfg.dtype], 8 * ULP[cfg.dtype])
+    assert ok, "h: max err %g, %d of %d out of tolerance" % (worst, nbad, got.size)
+    assert np.abs(want - lo.load(h0_st[rows], cfg.dtype)).max() > 1.0
+    gp.pool.close()
