@@ -254,14 +254,19 @@ def test_two_layer_stack_with_per_layer_pools():
     assert (np.isfinite(a) == np.isfinite(b)).all() and np.abs(a[m] - b[m]).max() <= 16 * ULP[cfg.dtype] * max(1.0, np.abs(b[m]).max())
 
 
-def test_7b_layer_full_size_against_the_oracle_on_two_sequences():
-    """One decoder layer at the benchmark's size (7B shapes: hidden 4096, 32 heads, MLP 11008, LoRA rank 16 on q, k,
-    v, o; the 18 953-token batch, the 4 GiB pool).  A token's output depends only on its own sequence, so the oracle
-    runs the layer on two of the 64 sequences and their rows of the GPU's full-batch result are compared."""
+@pytest.mark.parametrize("workload,n_oracle_seqs", [("7b_prefill", 2), ("7b_decode", 6)])
+def test_7b_layer_full_size_against_the_oracle_on_a_few_sequences(workload, n_oracle_seqs):
+    """One decoder layer at the benchmark's sizes (7B shapes: hidden 4096, 32 heads, MLP 11008, LoRA on q, k, v, o):
+    the 18 953-token prefill batch on the 4 GiB pool (large-batch GEMMs with the LoRA branch and the gate inside) and
+    the 256-token decode batch over contexts of 512-4096 (split small-batch GEMMs, per-token LoRA kernels).  A
+    token's output depends only on its own sequence, so the oracle runs the layer on a few of the sequences and their
+    rows of the GPU's full-batch result are compared."""
     import types
     import torch
     from paper_2505_03756_amd.harness import SparseGpuPool, compact_step
-    cfg = wl.config("7b_prefill")
+    cfg = wl.config(workload)
+    if workload == "7b_decode":
+        cfg = cfg.scaled(n_dev_blocks=40000)
     step = wl.make_step(cfg)
     T = step.n_tokens
     gp = SparseGpuPool(step)
@@ -291,8 +296,10 @@ def test_7b_layer_full_size_against_the_oracle_on_two_sequences():
     torch.cuda.synchronize()
     got_all = to_np(h, h0_st.dtype)
 
-    # the oracle on the longest-context sequence and the last one (whose rows end the batch's last, partly filled tile)
-    seqs = sorted({int(np.argmax(step.prefix_len + np.diff(step.cu_new))), cfg.n_seqs - 1})
+    # the oracle on the longest-context sequence, the last one (whose rows end the batch's last, partly filled tile)
+    # and, for the decode batch, a few more
+    seqs = sorted({int(np.argmax(step.prefix_len + np.diff(step.cu_new))), cfg.n_seqs - 1} |
+                  set(int(i) for i in rng.choice(cfg.n_seqs, size=n_oracle_seqs - 2, replace=False)))
     rows = np.concatenate([np.arange(step.cu_new[i], step.cu_new[i + 1]) for i in seqs])
     lens = np.array([step.cu_new[i + 1] - step.cu_new[i] for i in seqs])
     sub = types.SimpleNamespace(n_tokens=int(lens.sum()), proj={n: step.proj[n] for n in cfg.projections},
