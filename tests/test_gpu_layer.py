@@ -254,11 +254,13 @@ def test_two_layer_stack_with_per_layer_pools():
     assert (np.isfinite(a) == np.isfinite(b)).all() and np.abs(a[m] - b[m]).max() <= 16 * ULP[cfg.dtype] * max(1.0, np.abs(b[m]).max())
 
 
-@pytest.mark.parametrize("workload,n_oracle_seqs", [("7b_prefill", 2), ("7b_decode", 6)])
-def test_7b_layer_full_size_against_the_oracle_on_a_few_sequences(workload, n_oracle_seqs):
-    """One decoder layer at the benchmark's sizes (7B shapes: hidden 4096, 32 heads, MLP 11008, LoRA on q, k, v, o):
+@pytest.mark.parametrize("workload,n_oracle_seqs", [("7b_prefill", 2), ("7b_decode", 6), ("13b", 2), ("34b_gqa", 3)])
+def test_layer_full_size_against_the_oracle_on_a_few_sequences(workload, n_oracle_seqs):
+    """One decoder layer at the benchmark's sizes.  7B shapes (hidden 4096, 32 heads, MLP 11008, LoRA on q, k, v, o):
     the 18 953-token prefill batch on the 4 GiB pool (large-batch GEMMs with the LoRA branch and the gate inside) and
-    the 256-token decode batch over contexts of 512-4096 (split small-batch GEMMs, per-token LoRA kernels).  A
+    the 256-token decode batch over contexts of 512-4096 (split small-batch GEMMs, per-token LoRA kernels); the 13B
+    batch (rank 32 on seven projections: gate and up with their branches in one gated pass) and a quarter of the 34B
+    batch (grouped-query attention, rank 64, prefill and decode sequences mixed, contexts up to 16 k).  A
     token's output depends only on its own sequence, so the oracle runs the layer on a few of the sequences and their
     rows of the GPU's full-batch result are compared."""
     import types
@@ -267,6 +269,10 @@ def test_7b_layer_full_size_against_the_oracle_on_a_few_sequences(workload, n_or
     cfg = wl.config(workload)
     if workload == "7b_decode":
         cfg = cfg.scaled(n_dev_blocks=40000)
+    elif workload == "13b":         # hidden 5120, MLP 13824, rank 32 on all seven projections; 42 868 tokens
+        cfg = cfg.scaled(n_dev_blocks=65536, n_host_blocks=32768)
+    elif workload == "34b_gqa":     # hidden 8192, 64 query / 8 kv heads, MLP 22016, rank 64; a quarter of the sequences
+        cfg = cfg.scaled(n_seqs=128, n_dev_blocks=200000, n_host_blocks=32768)
     step = wl.make_step(cfg)
     T = step.n_tokens
     gp = SparseGpuPool(step)
@@ -275,17 +281,17 @@ def test_7b_layer_full_size_against_the_oracle_on_a_few_sequences(workload, n_or
     g.pool.swap_in(step.swap_in_host, step.swap_in_dev)
     torch.cuda.synchronize()
     rng = np.random.default_rng(11)
-    mlp = 11008
-    dims = {"q": (4096, 4096), "k": (4096, 4096), "v": (4096, 4096), "o": (4096, 4096), "gate": (mlp, 4096),
-            "up": (mlp, 4096), "down": (4096, mlp)}
-    W = {"in_norm": rng.normal(1, 0.1, 4096), "post_norm": rng.normal(1, 0.1, 4096)}
+    H, qd, kd = cfg.hidden, cfg.n_q_heads * cfg.head_dim, cfg.n_kv_heads * cfg.head_dim
+    mlp = cfg.mlp_dim or {4096: 11008, 8192: 22016}[H]
+    dims = {"q": (qd, H), "k": (kd, H), "v": (kd, H), "o": (H, qd), "gate": (mlp, H), "up": (mlp, H), "down": (H, mlp)}
+    W = {"in_norm": rng.normal(1, 0.1, H), "post_norm": rng.normal(1, 0.1, H)}
     for n, (d_out, d_in) in dims.items():
         W[n] = rng.standard_normal((d_out, d_in), dtype=np.float32) / np.float32(math.sqrt(d_in))
     W = {k: lo.round_store(v, cfg.dtype)[0] for k, v in W.items()}
-    h0_st, _ = lo.round_store(rng.standard_normal((T, 4096), dtype=np.float32), cfg.dtype)
+    h0_st, _ = lo.round_store(rng.standard_normal((T, H), dtype=np.float32), cfg.dtype)
     pos = np.concatenate([step.prefix_len[i] + np.arange(step.cu_new[i + 1] - step.cu_new[i])
                           for i in range(cfg.n_seqs)]).astype(np.int32)
-    layer = fllayer.Layer(g.pool, 4096, cfg.n_q_heads, mlp, {k: to_dev(v) for k, v in W.items()})
+    layer = fllayer.Layer(g.pool, H, cfg.n_q_heads, mlp, {k: to_dev(v) for k, v in W.items()})
     batch = fllayer.Batch(step.cu_new, step.prefix_len, to_dev(pos), g.kv_tables, g.token_adapter, g.rank, g.scale,
                           g.lora_tables, g.proj, n_adapters=len(step.rank), max_rank=int(step.rank.max()),
                           max_blocks_per_seq=step.kv_tables.shape[1])
