@@ -258,8 +258,8 @@ def test_two_layer_stack_with_per_layer_pools():
 def test_layer_full_size_against_the_oracle_on_a_few_sequences(workload, n_oracle_seqs):
     """One decoder layer at the benchmark's sizes.  7B shapes (hidden 4096, 32 heads, MLP 11008, LoRA on q, k, v, o):
     the 18 953-token prefill batch on the 4 GiB pool (large-batch GEMMs with the LoRA branch and the gate inside) and
-    the 256-token decode batch over contexts of 512-4096 (split small-batch GEMMs, per-token LoRA kernels); the 13B
-    batch (rank 32 on seven projections: gate and up with their branches in one gated pass) and a quarter of the 34B
+    the 256-token decode batch over contexts of 512-4096 (split small-batch GEMMs, per-token LoRA kernels); half of
+    the 13B batch (rank 32 on seven projections: gate and up with their branches in one gated pass) and a quarter of the 34B
     batch (grouped-query attention, rank 64, prefill and decode sequences mixed, contexts up to 16 k).  A
     token's output depends only on its own sequence, so the oracle runs the layer on a few of the sequences and their
     rows of the GPU's full-batch result are compared."""
@@ -269,8 +269,8 @@ def test_layer_full_size_against_the_oracle_on_a_few_sequences(workload, n_oracl
     cfg = wl.config(workload)
     if workload == "7b_decode":
         cfg = cfg.scaled(n_dev_blocks=40000)
-    elif workload == "13b":         # hidden 5120, MLP 13824, rank 32 on all seven projections; 42 868 tokens
-        cfg = cfg.scaled(n_dev_blocks=65536, n_host_blocks=32768)
+    elif workload == "13b":         # hidden 5120, MLP 13824, rank 32 on all seven projections; half of the sequences
+        cfg = cfg.scaled(n_seqs=64, n_dev_blocks=65536, n_host_blocks=32768)
     elif workload == "34b_gqa":     # hidden 8192, 64 query / 8 kv heads, MLP 22016, rank 64; a quarter of the sequences
         cfg = cfg.scaled(n_seqs=128, n_dev_blocks=200000, n_host_blocks=32768)
     step = wl.make_step(cfg)
