@@ -15,6 +15,8 @@
 // fp32 pools: a plain one-thread-per-output kernel (the fp32 workload is tiny).
 #include <hip/hip_runtime.h>
 
+#include <type_traits>
+
 #include "flp_internal.h"
 #include "flp_types.h"
 
@@ -444,44 +446,58 @@ __global__ __launch_bounds__(256, 1) void gemm_nt256_kernel(const uint16_t* __re
   }
 
   if constexpr (GATED) {
-    // the up waves' 256 accumulator values per lane, [token half][value][lane] in the 128 KiB the stages leave
-    float* xch = reinterpret_cast<float*>(smem) + (wj * 256) * 64 + lane;
+    // The gate wave and the up wave of a token half split the gating between them: the gate wave hands over its
+    // feature tiles 2, 3 and finishes tiles 0, 1, the up wave the other way round (128 accumulator values per lane
+    // each way, [wave][value][lane] in the 128 KiB the stages leave), so all four waves share the element-wise work.
+    float* const xbase = reinterpret_cast<float*>(smem) + lane;
+    float* const xown = xbase + (wave * 128) * 64;
+    const float* const xother = xbase + ((wave ^ 1) * 128) * 64;
     __syncthreads();                                       // everybody's loads have landed, nobody reads fragments any more
-    if (wi == 1) {
+    auto send = [&](auto i0) {                             // feature tiles i0, i0 + 1 of this wave
+      constexpr int I0 = decltype(i0)::value;
 #pragma unroll
-      for (int i = 0; i < 4; ++i)
+      for (int ii = 0; ii < 2; ++ii)
 #pragma unroll
         for (int j = 0; j < 4; ++j)
 #pragma unroll
-          for (int e = 0; e < 16; ++e) xch[((i * 4 + j) * 16 + e) * 64] = acc[i][j][e];
-    }
-    __syncthreads();
-    if (wi == 1) return;
+          for (int e = 0; e < 16; ++e) xown[((ii * 4 + j) * 16 + e) * 64] = acc[I0 + ii][j][e];
+    };
+    auto finish = [&](auto i0, auto own_is_gate) {         // feature tiles i0, i0 + 1: own values and the partner's
+      constexpr int I0 = decltype(i0)::value;
+      constexpr bool OWN_GATE = decltype(own_is_gate)::value;
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      const int m = m0 + 128 * wj + 32 * j + acol;
+      for (int j = 0; j < 4; ++j) {
+        const int m = m0 + 128 * wj + 32 * j + acol;
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const int n = n0 + 32 * i + 16 * hf;
-        uint16_t o[16];
+        for (int ii = 0; ii < 2; ++ii) {
+          const int n = n0 + 32 * (I0 + ii) + 16 * hf;
+          uint16_t o[16];
 #pragma unroll
-        for (int e = 0; e < 16; ++e) {
-          const float g = G::in(G::out(acc[i][j][e])), u = G::in(G::out(xch[((i * 4 + j) * 16 + e) * 64]));
-          o[e] = G::out(g / (1.0f + expf(-g)) * u);
-        }
-        if (m >= M || n >= N) continue;
-        uint16_t* yp = y + (int64_t)m * ld_y + n;
-        if (n + 16 <= N) {
-          u32x4 raw[2];
-          __builtin_memcpy(raw, o, 32);
-          reinterpret_cast<u32x4*>(yp)[0] = raw[0];
-          reinterpret_cast<u32x4*>(yp)[1] = raw[1];
-        } else {
-          for (int e = 0; e < 16; ++e)
-            if (n + e < N) yp[e] = o[e];
+          for (int e = 0; e < 16; ++e) {
+            const float own = G::in(G::out(acc[I0 + ii][j][e]));
+            const float oth = G::in(G::out(xother[((ii * 4 + j) * 16 + e) * 64]));
+            const float g = OWN_GATE ? own : oth, u = OWN_GATE ? oth : own;
+            o[e] = G::out(g / (1.0f + expf(-g)) * u);
+          }
+          if (m >= M || n >= N) continue;
+          uint16_t* yp = y + (int64_t)m * ld_y + n;
+          if (n + 16 <= N) {
+            u32x4 raw[2];
+            __builtin_memcpy(raw, o, 32);
+            reinterpret_cast<u32x4*>(yp)[0] = raw[0];
+            reinterpret_cast<u32x4*>(yp)[1] = raw[1];
+          } else {
+            for (int e = 0; e < 16; ++e)
+              if (n + e < N) yp[e] = o[e];
+          }
         }
       }
-    }
+    };
+    using I0c = std::integral_constant<int, 0>;
+    using I2c = std::integral_constant<int, 2>;
+    if (wi == 0) send(I2c{}); else send(I0c{});
+    __syncthreads();
+    if (wi == 0) finish(I0c{}, std::true_type{}); else finish(I2c{}, std::false_type{});
     return;
   }
 
