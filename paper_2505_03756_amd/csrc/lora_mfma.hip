@@ -205,11 +205,16 @@ constexpr int lvmcnt(int n) { return (n & 15) | ((n >> 4) << 14) | (7 << 4) | (1
 template <typename L, int NT>
 __global__ __launch_bounds__(256) void lora_shrink_lds_kernel(FlpLoraArgs a, FlpLoraMfma c) {
   typedef typename L::vec vec;
+  // From rank 33 on a workgroup takes TWO neighbouring 32-token tiles of a segment (the first of each pair does
+  // the work, the second exits): the adapter's A rows, which at rank 64 are twice the bytes of a 32-token x tile,
+  // are then fetched once per 64 tokens (34B shapes: q,k,v call 1.47 -> 1.25 ms; at rank 32 it does not pay).
+  constexpr int XT = NT >= 4 ? 4 : 2;                  // 16-token tiles per workgroup
   constexpr int kS = 4;                                // ring stages
-  constexpr int kStageB = 4096 + 2048 * NT;            // x rows, then A rows, 128 bytes each
-  constexpr int NINS = 4 + 2 * NT;                     // 1 KiB load instructions per chunk (8 rows each)
+  constexpr int kXB = 2048 * XT;                       // bytes of the x rows of a stage
+  constexpr int kStageB = kXB + 2048 * NT;             // x rows, then A rows, 128 bytes each
+  constexpr int NINS = 2 * XT + 2 * NT;                // 1 KiB load instructions per chunk (8 rows each)
   constexpr int NPER = NINS / 4;                       // of which each wave issues this many
-  constexpr int NP = 2 * NT / 4;                       // (token tile, rank tile) pairs per wave
+  constexpr int NP = XT * NT / 4;                      // (16-token tile, rank tile) pairs per wave
   __shared__ __attribute__((aligned(1024))) uint8_t smem[kS * kStageB];
   const int n_seg = *a.n_seg;
   const int n_tiles = a.tile_start[n_seg];
@@ -226,6 +231,8 @@ __global__ __launch_bounds__(256) void lora_shrink_lds_kernel(FlpLoraArgs a, Flp
     const int tile = (blockIdx.x & 7) * per_xcd + lt;
     if (tile >= n_tiles) break;
     const int s = find_segment(a.tile_start, n_seg, tile);
+    if (XT == 4 && ((tile - a.tile_start[s]) & 1)) continue;     // the second tile of a pair: its neighbour does it
+    const bool second = XT == 4 && tile + 1 < a.tile_start[s + 1];  // the pair is complete
     const int ad = a.seg_adapter[s];
     const int r = a.rank[ad] < 16 * NT ? a.rank[ad] : 16 * NT;
     const int pos0 = a.seg_start[s] + (tile - a.tile_start[s]) * 32;
@@ -235,7 +242,7 @@ __global__ __launch_bounds__(256) void lora_shrink_lds_kernel(FlpLoraArgs a, Flp
     const int n_chunks = r > 0 ? (kend - kbeg) / 64 : 0;
 
     // ---- this lane's rows of the load instructions it issues: instruction j = wave + 4 i covers rows
-    //      8 j .. 8 j + 7 of the x tile (j < 4) or rows 8 (j - 4) .. of the A tile; lane l holds row l / 8,
+    //      8 j .. 8 j + 7 of the x rows (j < 2 XT) or rows 8 (j - 2 XT) .. of the A tile; lane l holds row l / 8,
     //      LDS slot l % 8, i.e. the row's logical 16-byte piece (l % 8) ^ (row % 8)
     uint64_t gaddr[NPER];
     uint32_t ldst[NPER];
@@ -244,20 +251,20 @@ __global__ __launch_bounds__(256) void lora_shrink_lds_kernel(FlpLoraArgs a, Flp
       const int j = wave + 4 * i, rl = lane >> 3;
       const uint16_t* rowp;
       int rowi;
-      if (j < 4) {
+      if (j < 2 * XT) {
         rowi = 8 * j + rl;
         int pos = pos0 + rowi;
         pos = pos < pos_end ? pos : pos_end - 1;       // padding rows repeat the last token
         rowp = reinterpret_cast<const uint16_t*>(a.x) + (int64_t)a.perm[pos] * a.ld_x;
         ldst[i] = 1024u * j;
       } else {
-        rowi = 8 * (j - 4) + rl;
+        rowi = 8 * (j - 2 * XT) + rl;
         rowp = pool;
         if (r > 0) {
           const int ii = pr.a_row_base[ad] + (rowi < r ? rowi : 0);
           rowp = pool + (int64_t)a.tables[pr.a_tab_off[ad] + ii / rpb] * a.block_elems + (int64_t)(ii % rpb) * a.d_in;
         }
-        ldst[i] = 4096u + 1024u * (j - 4);
+        ldst[i] = (uint32_t)kXB + 1024u * (j - 2 * XT);
       }
       gaddr[i] = (uint64_t)(uintptr_t)(rowp + kbeg + 8 * ((lane & 7) ^ (rowi & 7)));
     }
@@ -276,7 +283,7 @@ __global__ __launch_bounds__(256) void lora_shrink_lds_kernel(FlpLoraArgs a, Flp
       const int pi = wave + 4 * i, mt = pi / NT, nt = pi % NT;
       const int xr = 16 * mt + row16, ar = 16 * nt + row16;
       offx[i] = xr * 128 + ((kg ^ (xr & 7)) << 4);                 // k step 0; step 1 is slot + 4: offset ^ 64
-      offa[i] = 4096 + ar * 128 + ((kg ^ (ar & 7)) << 4);
+      offa[i] = kXB + ar * 128 + ((kg ^ (ar & 7)) << 4);
     }
 
     __builtin_amdgcn_s_waitcnt(lvmcnt(0));             // the loads above are in: only chunk loads are in flight below
@@ -301,12 +308,14 @@ __global__ __launch_bounds__(256) void lora_shrink_lds_kernel(FlpLoraArgs a, Flp
     }
     __builtin_amdgcn_s_waitcnt(lvmcnt(0));             // look-ahead loads past the last chunk must land before the ring is reused
 
-    // lane (rank column n = lane % 16, token rows 4 kg .. 4 kg + 3) of each pair
+    // lane (rank column n = lane % 16, token rows 4 kg .. 4 kg + 3) of each pair; the rows of the pair's second tile
+    // follow the first one's in v
     const int RP = 16 * NT;
     float* __restrict__ vout = a.v + ((int64_t)ks * c.v_rows + (int64_t)tile * 32) * a.n_proj * RP;
 #pragma unroll
     for (int i = 0; i < NP; ++i) {
       const int pi = wave + 4 * i, mt = pi / NT, nt = pi % NT;
+      if (mt >= 2 && !second) continue;
 #pragma unroll
       for (int e = 0; e < 4; ++e)
         vout[((int64_t)(16 * mt + 4 * kg + e) * a.n_proj + p) * RP + 16 * nt + row16] = acc[i][e];
