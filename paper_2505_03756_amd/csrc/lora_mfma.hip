@@ -681,6 +681,17 @@ __global__ __launch_bounds__(256) void lora_expand_lds_kernel(FlpLoraArgs a, Flp
       const int tok = a.perm[tvalid ? pos : pos_stop - 1];
       uint16_t* yrow = reinterpret_cast<uint16_t*>(pr.y) + (int64_t)tok * pr.ld_y + slab_begin + 16 * kg;
       const float* brow = a.base32[p] ? a.base32[p] + (int64_t)tok * pr.d_out + slab_begin + 16 * kg : nullptr;
+      // the y pieces of all four chunks are requested first, so that their latency overlaps the preparation of v
+      // and four chunks per wave are in flight instead of one
+      u32x4 yall[4][2];
+      if (!brow) {
+#pragma unroll
+        for (int ch = 0; ch < 4; ++ch)
+          if (slab_begin + 64 * ch < pr.d_out) {
+            yall[ch][0] = *reinterpret_cast<const u32x4*>(yrow + 64 * ch);
+            yall[ch][1] = *reinterpret_cast<const u32x4*>(yrow + 64 * ch + 8);
+          }
+      }
       // ---- B operand: this token's scaled v for all rank tiles, high part in k-slots 0..15, remainder in 16..31
       vec vb[NT];
 #pragma unroll
@@ -712,11 +723,6 @@ __global__ __launch_bounds__(256) void lora_expand_lds_kernel(FlpLoraArgs a, Flp
 #pragma unroll
       for (int ch = 0; ch < 4; ++ch) {
         if (slab_begin + 64 * ch >= pr.d_out) continue;
-        u32x4 yraw[2];
-        if (!brow) {
-          yraw[0] = *reinterpret_cast<const u32x4*>(yrow + 64 * ch);
-          yraw[1] = *reinterpret_cast<const u32x4*>(yrow + 64 * ch + 8);
-        }
         f32x4 acc[4];
 #pragma unroll
         for (int tau = 0; tau < 4; ++tau) {
@@ -741,7 +747,7 @@ __global__ __launch_bounds__(256) void lora_expand_lds_kernel(FlpLoraArgs a, Flp
               for (int i = 0; i < 4; ++i) ys[4 * tau + i] = S::from_float(b4[i] + acc[tau][i]);
             }
           } else {
-            __builtin_memcpy(ys, &yraw[0], 32);
+            __builtin_memcpy(ys, &yall[ch][0], 32);
 #pragma unroll
             for (int tau = 0; tau < 4; ++tau)
 #pragma unroll
