@@ -202,29 +202,35 @@ __device__ __forceinline__ void lload_lds16(uint64_t addr, uint32_t lds) {
 }
 constexpr int lvmcnt(int n) { return (n & 15) | ((n >> 4) << 14) | (7 << 4) | (15 << 8); }   // s_waitcnt vmcnt(n) only
 
-template <typename L, int NT>
+template <typename L, int NT, int NPJ>
 __global__ __launch_bounds__(256) void lora_shrink_lds_kernel(FlpLoraArgs a, FlpLoraMfma c) {
   typedef typename L::vec vec;
   // From rank 33 on a workgroup takes TWO neighbouring 32-token tiles of a segment (the first of each pair does
   // the work, the second exits): the adapter's A rows, which at rank 64 are twice the bytes of a 32-token x tile,
   // are then fetched once per 64 tokens (34B shapes: q,k,v call 1.47 -> 1.25 ms; at rank 32 it does not pay).
+  // NPJ = 2, 3 (used with two rank tiles): the projections of the call are fused (their A rows sit behind each
+  // other in a stage, x is fetched once for all of them); NPJ = 1: one projection per workgroup, taken from the
+  // grid.
   constexpr int XT = NT >= 4 ? 4 : 2;                  // 16-token tiles per workgroup
   constexpr int kS = 4;                                // ring stages
   constexpr int kXB = 2048 * XT;                       // bytes of the x rows of a stage
-  constexpr int kStageB = kXB + 2048 * NT;             // x rows, then A rows, 128 bytes each
-  constexpr int NINS = 2 * XT + 2 * NT;                // 1 KiB load instructions per chunk (8 rows each)
+  constexpr int kAB = 2048 * NT;                       // bytes of one projection's A rows
+  constexpr int kStageB = kXB + NPJ * kAB;             // x rows, then A rows, 128 bytes each
+  constexpr int NINS = 2 * XT + 2 * NT * NPJ;          // 1 KiB load instructions per chunk (8 rows each)
+  static_assert(NINS % 4 == 0, "the waves share the load instructions of a chunk evenly");
   constexpr int NPER = NINS / 4;                       // of which each wave issues this many
-  constexpr int NP = XT * NT / 4;                      // (16-token tile, rank tile) pairs per wave
+  constexpr int NP = XT * NT * NPJ / 4;                // (projection, 16-token tile, rank tile) triples per wave
+  static_assert(kS * kStageB <= 65536, "the ring fits the LDS of a static array");
   __shared__ __attribute__((aligned(1024))) uint8_t smem[kS * kStageB];
   const int n_seg = *a.n_seg;
   const int n_tiles = a.tile_start[n_seg];
   const int per_xcd = (n_tiles + 7) / 8;
-  const int per_tile = c.k_splits * a.n_proj;
-  const int ks = ((blockIdx.x >> 3) % per_tile) / a.n_proj, p = ((blockIdx.x >> 3) % per_tile) % a.n_proj;
+  const int per_tile = c.k_splits * (NPJ == 1 ? a.n_proj : 1);
+  const int ks = NPJ == 1 ? ((blockIdx.x >> 3) % per_tile) / a.n_proj : (blockIdx.x >> 3) % per_tile;
+  const int p0 = NPJ == 1 ? ((blockIdx.x >> 3) % per_tile) % a.n_proj : 0;       // first (only) projection of this workgroup
   const int tid = threadIdx.x, lane = tid & 63, row16 = lane & 15, kg = lane >> 4;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const uint16_t* __restrict__ pool = reinterpret_cast<const uint16_t*>(a.pool);
-  const flp_lora_proj& pr = a.proj[p];
   const int rpb = (int)(a.block_elems / a.d_in);
   const uint32_t lds0 = (uint32_t)(uintptr_t)(l_lds_u8*)smem;
   for (int lt = (blockIdx.x >> 3) / per_tile; lt < per_xcd; lt += (gridDim.x >> 3) / per_tile) {
@@ -242,8 +248,9 @@ __global__ __launch_bounds__(256) void lora_shrink_lds_kernel(FlpLoraArgs a, Flp
     const int n_chunks = r > 0 ? (kend - kbeg) / 64 : 0;
 
     // ---- this lane's rows of the load instructions it issues: instruction j = wave + 4 i covers rows
-    //      8 j .. 8 j + 7 of the x rows (j < 2 XT) or rows 8 (j - 2 XT) .. of the A tile; lane l holds row l / 8,
-    //      LDS slot l % 8, i.e. the row's logical 16-byte piece (l % 8) ^ (row % 8)
+    //      8 j .. 8 j + 7 of the x rows (j < 2 XT) or, for jj = j - 2 XT, rows 8 (jj % 2 NT) .. of the A tile of
+    //      projection jj / 2 NT; lane l holds row l / 8, LDS slot l % 8, i.e. the row's logical 16-byte piece
+    //      (l % 8) ^ (row % 8)
     uint64_t gaddr[NPER];
     uint32_t ldst[NPER];
 #pragma unroll
@@ -258,13 +265,15 @@ __global__ __launch_bounds__(256) void lora_shrink_lds_kernel(FlpLoraArgs a, Flp
         rowp = reinterpret_cast<const uint16_t*>(a.x) + (int64_t)a.perm[pos] * a.ld_x;
         ldst[i] = 1024u * j;
       } else {
-        rowi = 8 * (j - 2 * XT) + rl;
+        const int jj = j - 2 * XT, pj = jj / (2 * NT), jr = jj % (2 * NT);
+        const flp_lora_proj& pr = a.proj[p0 + pj];
+        rowi = 8 * jr + rl;
         rowp = pool;
         if (r > 0) {
           const int ii = pr.a_row_base[ad] + (rowi < r ? rowi : 0);
           rowp = pool + (int64_t)a.tables[pr.a_tab_off[ad] + ii / rpb] * a.block_elems + (int64_t)(ii % rpb) * a.d_in;
         }
-        ldst[i] = (uint32_t)kXB + 1024u * (j - 2 * XT);
+        ldst[i] = (uint32_t)(kXB + pj * kAB) + 1024u * jr;
       }
       gaddr[i] = (uint64_t)(uintptr_t)(rowp + kbeg + 8 * ((lane & 7) ^ (rowi & 7)));
     }
@@ -280,10 +289,10 @@ __global__ __launch_bounds__(256) void lora_shrink_lds_kernel(FlpLoraArgs a, Flp
 #pragma unroll
     for (int i = 0; i < NP; ++i) {
       acc[i] = f32x4{0.f, 0.f, 0.f, 0.f};
-      const int pi = wave + 4 * i, mt = pi / NT, nt = pi % NT;
+      const int pi = wave + 4 * i, pj = pi / (XT * NT), mt = (pi % (XT * NT)) / NT, nt = pi % NT;
       const int xr = 16 * mt + row16, ar = 16 * nt + row16;
       offx[i] = xr * 128 + ((kg ^ (xr & 7)) << 4);                 // k step 0; step 1 is slot + 4: offset ^ 64
-      offa[i] = kXB + ar * 128 + ((kg ^ (ar & 7)) << 4);
+      offa[i] = kXB + pj * kAB + ar * 128 + ((kg ^ (ar & 7)) << 4);
     }
 
     __builtin_amdgcn_s_waitcnt(lvmcnt(0));             // the loads above are in: only chunk loads are in flight below
@@ -308,17 +317,17 @@ __global__ __launch_bounds__(256) void lora_shrink_lds_kernel(FlpLoraArgs a, Flp
     }
     __builtin_amdgcn_s_waitcnt(lvmcnt(0));             // look-ahead loads past the last chunk must land before the ring is reused
 
-    // lane (rank column n = lane % 16, token rows 4 kg .. 4 kg + 3) of each pair; the rows of the pair's second tile
-    // follow the first one's in v
+    // lane (rank column n = lane % 16, token rows 4 kg .. 4 kg + 3) of each triple; the rows of the pair's second
+    // tile follow the first one's in v
     const int RP = 16 * NT;
     float* __restrict__ vout = a.v + ((int64_t)ks * c.v_rows + (int64_t)tile * 32) * a.n_proj * RP;
 #pragma unroll
     for (int i = 0; i < NP; ++i) {
-      const int pi = wave + 4 * i, mt = pi / NT, nt = pi % NT;
+      const int pi = wave + 4 * i, pj = pi / (XT * NT), mt = (pi % (XT * NT)) / NT, nt = pi % NT;
       if (mt >= 2 && !second) continue;
 #pragma unroll
       for (int e = 0; e < 4; ++e)
-        vout[((int64_t)(16 * mt + 4 * kg + e) * a.n_proj + p) * RP + 16 * nt + row16] = acc[i][e];
+        vout[((int64_t)(16 * mt + 4 * kg + e) * a.n_proj + p0 + pj) * RP + 16 * nt + row16] = acc[i][e];
     }
   }
 }
@@ -777,8 +786,18 @@ flp_status launch_pair(const FlpLoraArgs& a, const FlpLoraMfma& c, hipStream_t s
   bool staged = false;
   if constexpr (NT >= 2 && MT == 2) {
     if (a.d_in % 64 == 0) {
-      hipLaunchKernelGGL((lora_shrink_lds_kernel<L, NT>), dim3((unsigned)(c.tiles_grid * c.k_splits * a.n_proj)),
-                         dim3(256), 0, stream, a, c);
+      // two rank tiles: the projections of a call with two or three of them are fused (13B shapes, q,k,v call:
+      // 0.89 -> 0.86 ms); with four rank tiles the fused stages leave one workgroup per CU and the call takes
+      // twice as long (34B shapes: 1.25 -> 2.35 ms), so there a workgroup keeps to one projection
+      constexpr int NPJ2 = NT == 2 ? 2 : 1, NPJ3 = NT == 2 ? 3 : 1;
+      const dim3 gf((unsigned)(c.tiles_grid * c.k_splits));
+      if (NT == 2 && a.n_proj == 2)
+        hipLaunchKernelGGL((lora_shrink_lds_kernel<L, NT, NPJ2>), gf, dim3(256), 0, stream, a, c);
+      else if (NT == 2 && a.n_proj == 3)
+        hipLaunchKernelGGL((lora_shrink_lds_kernel<L, NT, NPJ3>), gf, dim3(256), 0, stream, a, c);
+      else
+        hipLaunchKernelGGL((lora_shrink_lds_kernel<L, NT, 1>), dim3((unsigned)(c.tiles_grid * c.k_splits * a.n_proj)),
+                           dim3(256), 0, stream, a, c);
       staged = true;
     }
   }
