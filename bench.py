@@ -299,6 +299,13 @@ def main():
             k["flops"] = int(k["flops"])
         k["bytes"] = int(k["bytes"])
 
+    # ---- what this machine reaches with no arithmetic at all: a device-to-device copy and a pinned host-to-device
+    #      copy (the runtime's own copy routines), the second denominator of every stage
+    ach = achievable_rates(s_comp)
+    for name, k in kernels.items():
+        den = ach["pcie_h2d_GBps"] if k["bound"] == "pcie" else ach["hbm_copy_GBps"]
+        k["frac_of_achievable"] = round(k["GBps"] / den, 4) if k["GBps"] else None
+
     # dominant on-chip kernel = attention; report it against the roofline that binds it
     a = kernels["attention"]
     t_hbm = a["bytes"] / (HBM_PEAK_GBS * 1e9)
@@ -382,6 +389,7 @@ def main():
                             if n_sets == 2 else "none in this workload")},
         "roofline": roof,
         "kernels": kernels,
+        "achievable": ach,
         "serialised": {"ms_per_step": round(serial_ms, 4), "tokens_per_s": round(T / (serial_ms * 1e-3), 1),
                        "compute_only_ms": round(compute_ms, 4),
                        "compute_only_tokens_per_s": round(T / (compute_ms * 1e-3), 1)},
@@ -394,6 +402,39 @@ def main():
         out["host_logic"] = host_logic()
         out["cpu_baseline"] = cpu_baseline(wl.make_step(cfg, seed=seed), args.cpu_seconds)
     print(json.dumps(out))
+
+
+def achievable_rates(stream):
+    """Rates of plain copies on this machine, measured with HIP events on `stream`: 1 GiB device to device (read +
+    write counted, the way the HBM-bound stages count their bytes) and 512 MiB from pinned host memory to the
+    device.  Median of 5 after one warm-up each."""
+    import numpy as np
+    import torch
+    n_dev, n_host = 1 << 30, 1 << 29
+    src = torch.empty(n_dev, dtype=torch.uint8, device="cuda").fill_(1)
+    dst = torch.empty_like(src)
+    host = torch.empty(n_host, dtype=torch.uint8, pin_memory=True).fill_(1)
+
+    def med(f):
+        ts = []
+        with torch.cuda.stream(stream):
+            f()
+            for _ in range(5):
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record(stream)
+                f()
+                e1.record(stream)
+                e1.synchronize()
+                ts.append(e0.elapsed_time(e1))
+        return float(np.median(ts))
+    torch.cuda.synchronize()
+    t_copy = med(lambda: dst.copy_(src, non_blocking=True))
+    t_h2d = med(lambda: dst[:n_host].copy_(host, non_blocking=True))
+    torch.cuda.synchronize()
+    del src, dst, host
+    return {"hbm_copy_GBps": round(2 * n_dev / (t_copy * 1e6), 1), "pcie_h2d_GBps": round(n_host / (t_h2d * 1e6), 1),
+            "note": "1 GiB device-to-device copy (read + write bytes) and 512 MiB pinned host-to-device copy by the "
+                    "runtime's copy routines, median of 5"}
 
 
 def layer_stack(args, cfg, r0, stream):
