@@ -560,7 +560,15 @@ def cpu_baseline(step, target_s):
     n -= n % threads if n > threads else 0
     sel = rng.choice(T, size=n, replace=False).astype(np.int32)
     dt = run(sel)
-    return {"value": round(n / dt, 2), "unit": "tokens/s", "cores": threads, "kind": "oracle",
+    host = {"nproc": os.cpu_count()}
+    try:
+        with open("/proc/cpuinfo") as f:
+            host["cpu"] = next(l.split(":", 1)[1].strip() for l in f if l.startswith("model name"))
+        with open("/proc/meminfo") as f:
+            host["mem_GiB"] = round(int(next(l for l in f if l.startswith("MemTotal")).split()[1]) / 2 ** 20, 1)
+    except (OSError, StopIteration, ValueError):
+        pass
+    return {"value": round(n / dt, 2), "unit": "tokens/s", "cores": threads, "kind": "oracle", "host": host,
             "sample": "%d of %d tokens of one batch of the same workload (uniform, seeded): LoRA rows for %s and the "
                       "attention row over the full context, fp64, OpenMP over tokens; %.1f s"
                       % (n, T, "/".join(cfg.projections), dt)}
