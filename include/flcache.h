@@ -74,7 +74,9 @@ typedef struct {
   double last_use;
 } flc_node_info;
 
-/* The cache works on `pool` (kept by pointer; destroy the cache first).  Section 4.3. */
+/* The cache works on `pool` (kept by pointer; destroy the cache first).  flc_destroy returns the blocks that the
+ * nodes still hold to the pool (blocks of not_taken lists and of forgotten queries were the caller's already).
+ * Section 4.3. */
 flp_status flc_create(flp_pool* pool, const flc_config* cfg, flc_cache** out);
 flp_status flc_destroy(flc_cache* c);
 

@@ -190,6 +190,10 @@ extern "C" flp_status flc_create(flp_pool* pool, const flc_config* cfg, flc_cach
 }
 
 extern "C" flp_status flc_destroy(flc_cache* c) {
+  if (!c) return FLP_OK;
+  // the blocks that the nodes still hold go back to the pool, which outlives the cache
+  for (const Node& n : c->nodes)
+    if (n.alive && !n.blocks.empty()) (void)flp_pool_free(c->pool, n.tier, (int32_t)n.blocks.size(), n.blocks.data());
   delete c;
   return FLP_OK;
 }

@@ -207,3 +207,27 @@ def test_overheads_stay_within_the_papers_budget():
           (s["n_nodes"], mean_match * 1e3, max(t_match) * 1e3, len(od), t_tick * 1e3))
     assert mean_match < 0.5e-3
     assert t_tick < 5e-3
+
+
+def test_random_walk_over_the_host_abi_under_sanitizers(tmp_path):
+    """tests/cache_fuzz.cpp (a seeded random walk over every entry point of include/flcache.h, legal and illegal
+    arguments, all four policy variants, roomy and tight tiers) built from the library's own host sources with
+    AddressSanitizer and UndefinedBehaviorSanitizer: no report, block accounting intact after every call, blocks
+    back in the pool after flc_destroy."""
+    import shutil
+    import subprocess
+    gxx = shutil.which("g++")
+    if gxx is None:
+        pytest.skip("no g++")
+    csrc = os.path.join(ROOT, "paper_2505_03756_amd", "csrc")
+    exe = str(tmp_path / "cache_fuzz")
+    cmd = [gxx, "-std=c++17", "-O1", "-g", "-fsanitize=address,undefined", "-fno-sanitize-recover=undefined",
+           "-static-libasan", "-D__HIP_PLATFORM_AMD__", "-I" + os.path.join(ROOT, "include"), "-I" + csrc,
+           "-I/opt/rocm/include", os.path.join(ROOT, "tests", "cache_fuzz.cpp"), os.path.join(csrc, "pool.cpp"),
+           os.path.join(csrc, "cache_manager.cpp"), "-L/opt/rocm/lib", "-lamdhip64", "-Wl,-rpath,/opt/rocm/lib",
+           "-o", exe]
+    b = subprocess.run(cmd, capture_output=True, text=True, timeout=300)
+    assert b.returncode == 0, b.stderr[-3000:]
+    r = subprocess.run([exe, "3000"], capture_output=True, text=True, timeout=300)
+    assert r.returncode == 0, (r.stdout + r.stderr)[-3000:]
+    assert "accounting held after every call" in r.stdout
