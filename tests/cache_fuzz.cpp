@@ -3,7 +3,8 @@
 // it).  It checks no results against a model (the Python tests do that against the oracle); it drives every entry
 // point through many states, legal and illegal arguments included, so that the sanitizers see the code paths, and
 // it checks the accounting that must hold after every call: every block of a tier is either free or held by
-// exactly one node or by a running query's fresh blocks.
+// exactly one node or by a running query's fresh blocks.  A second walk drives the pool's own alloc / free / swap
+// calls against a set of held ids and through every argument check.
 #include <cstdint>
 #include <cstdio>
 #include <cstdlib>
@@ -224,6 +225,80 @@ void run(uint64_t seed, int n_ops, const flc_config& cfg, int64_t n_dev, int64_t
   std::free(host);
 }
 
+// The pool alone: seeded allocations and frees against a set of held ids, and every argument check of the
+// alloc / free / swap calls (the swap calls must refuse bad lists before they launch anything).
+void run_pool(uint64_t seed, int n_ops) {
+  std::mt19937_64 rng(seed);
+  auto uni = [&](int lo, int hi) { return (int)(lo + rng() % (uint64_t)(hi - lo + 1)); };
+  const int64_t n_blocks[2] = {40, 24};
+  flp_pool_config pc{};
+  pc.dtype = FLP_BF16;
+  pc.block_tokens = 16;
+  pc.n_kv_heads = 1;
+  pc.head_dim = 64;
+  pc.n_dev_blocks = n_blocks[0];
+  pc.n_host_blocks = n_blocks[1];
+  const size_t block_bytes = (size_t)2 * 16 * 64 * 2;
+  void* dev = std::aligned_alloc(256, block_bytes * (size_t)n_blocks[0]);
+  void* host = std::aligned_alloc(256, block_bytes * (size_t)n_blocks[1]);
+  REQUIRE(dev && host);
+  pc.dev_base = dev;
+  pc.host_base = host;
+  flp_pool* pool = nullptr;
+  REQUIRE(flp_pool_create(nullptr, &pool) == FLP_EINVAL && flp_pool_create(&pc, nullptr) == FLP_EINVAL);
+  pc.dev_base = (char*)dev + 8;
+  REQUIRE(flp_pool_create(&pc, &pool) == FLP_EINVAL);            // misaligned base
+  pc.dev_base = dev;
+  REQUIRE(flp_pool_create(&pc, &pool) == FLP_OK);
+  std::set<int32_t> held[2];
+  for (int op = 0; op < n_ops; ++op) {
+    const int tier = uni(0, 1), what = uni(0, 9);
+    if (what < 5) {
+      const int n = uni(0, 12);
+      std::vector<int32_t> ids((size_t)n + 1, -7);
+      const flp_status s = flp_pool_alloc(pool, tier, n, ids.data());
+      if (n > n_blocks[tier] - (int64_t)held[tier].size()) {
+        REQUIRE(s == FLP_ENOSPC && (n == 0 || ids[0] == -7));      // all or nothing
+      } else {
+        REQUIRE(s == FLP_OK);
+        for (int i = 0; i < n; ++i) {
+          REQUIRE(ids[(size_t)i] >= 0 && ids[(size_t)i] < n_blocks[tier]);
+          REQUIRE(held[tier].insert(ids[(size_t)i]).second);       // never an id that is held
+        }
+      }
+    } else if (what < 8 && !held[tier].empty()) {
+      std::vector<int32_t> ids;
+      for (int32_t id : held[tier])
+        if (uni(0, 2) == 0) ids.push_back(id);
+      REQUIRE(flp_pool_free(pool, tier, (int32_t)ids.size(), ids.data()) == FLP_OK);
+      for (int32_t id : ids) held[tier].erase(id);
+      if (!ids.empty()) REQUIRE(flp_pool_free(pool, tier, 1, ids.data()) == FLP_EDUP);   // free twice
+    } else {
+      int32_t bad[3] = {-1, (int32_t)n_blocks[tier], 0};
+      REQUIRE(flp_pool_free(pool, tier, 1, &bad[0]) == FLP_ERANGE && flp_pool_free(pool, tier, 1, &bad[1]) == FLP_ERANGE);
+      REQUIRE(flp_pool_free(pool, tier, -1, bad) == FLP_EINVAL && flp_pool_free(pool, 2, 1, bad) == FLP_EINVAL);
+      REQUIRE(flp_pool_alloc(pool, tier, -1, bad) == FLP_EINVAL && flp_pool_alloc(pool, tier, 1, nullptr) == FLP_EINVAL);
+      if (held[tier].size() >= 2) {                             // one id twice in a list: nothing is freed
+        int32_t twice[2] = {*held[tier].begin(), *held[tier].begin()};
+        REQUIRE(flp_pool_free(pool, tier, 2, twice) == FLP_EDUP);
+      }
+      // swap lists that must be refused before anything is launched
+      int32_t src[2] = {0, 1}, dup[2] = {3, 3}, far[2] = {0, (int32_t)n_blocks[0]};
+      REQUIRE(flp_pool_swap_in(pool, 2, src, dup, nullptr) == FLP_EDUP);
+      REQUIRE(flp_pool_swap_out(pool, 2, src, dup, nullptr) == FLP_EDUP);
+      REQUIRE(flp_pool_swap_in(pool, 2, src, far, nullptr) == FLP_ERANGE);
+      REQUIRE(flp_pool_swap_out(pool, 2, far, src, nullptr) == FLP_ERANGE);
+      REQUIRE(flp_pool_swap_in(pool, -1, src, src, nullptr) == FLP_EINVAL);
+      REQUIRE(flp_pool_swap_in(pool, 1, nullptr, src, nullptr) == FLP_EINVAL);
+      REQUIRE(flp_pool_swap_in(pool, 0, nullptr, nullptr, nullptr) == FLP_OK);
+    }
+    for (int t = 0; t < 2; ++t) REQUIRE(flp_pool_num_free(pool, t) + (int64_t)held[t].size() == n_blocks[t]);
+  }
+  REQUIRE(flp_pool_destroy(pool) == FLP_OK);
+  std::free(dev);
+  std::free(host);
+}
+
 }  // namespace
 
 int main(int argc, char** argv) {
@@ -245,6 +320,7 @@ int main(int argc, char** argv) {
       run(seed * 7919 + (uint64_t)variant, n_ops, cfg, n_dev, n_host);
       ++runs;
     }
+  for (uint64_t seed = 1; seed <= 3; ++seed) run_pool(seed, n_ops);
   std::printf("cache_fuzz: %d runs of %d calls, accounting held after every call; swapped out %ld, in %ld (by "
               "matches %ld), forgotten %ld, waiting queries %ld, matched blocks %ld, blocks given back %ld\n",
               runs, n_ops, seen.out, seen.in, seen.match_swaps, seen.dropped, seen.waiting, seen.matched_blocks,
