@@ -3,6 +3,8 @@ declares, and its free lists / argument validation agree with the oracle's alloc
 import ctypes as C
 import os
 import re
+import subprocess
+import sys
 
 import numpy as np
 import pytest
@@ -211,8 +213,6 @@ def test_pool_create_rejects_bad_geometry():
 
 
 def test_bench_refuses_more_than_one_gpu():
-    import subprocess
-    import sys
     r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True,
                        timeout=120)
     assert r.returncode == 2
@@ -241,3 +241,19 @@ x.hip:9:1: remark:     Occupancy [waves/SIMD]: 1 [-Rpass-analysis=kernel-resourc
     assert res["good_kernel"] == {"vgprs": 64, "agprs": 0, "scratch": 56, "occupancy": 8, "lds": 1024}
     assert res["bad_kernel"]["scratch"] == 1088 and res["bad_kernel"]["agprs"] == 256
     assert [k for k, v in res.items() if v["scratch"] > b.MAX_SCRATCH_BYTES] == ["bad_kernel"]
+
+
+def test_binding_fails_loudly_without_the_library(tmp_path):
+    """The product path has no fallback: with no built library the binding raises at load (in a fresh process, with
+    the library path pointed at a file that does not exist) instead of computing anything some other way."""
+    code = ("import sys; sys.path.insert(0, %r)\n"
+            "from paper_2505_03756_amd import flpool\n"
+            "flpool.LIB_PATH = %r\n"
+            "try:\n"
+            "    flpool.Pool('f16', 1, 64, 4, 4)\n"
+            "except flpool.FlpError as e:\n"
+            "    print('raised:', e); sys.exit(7)\n"
+            "sys.exit(0)\n") % (ROOT, str(tmp_path / "libflpool.so"))
+    r = subprocess.run([sys.executable, "-c", code], capture_output=True, text=True, timeout=120)
+    assert r.returncode == 7, r.stdout + r.stderr
+    assert "not built" in r.stdout
