@@ -63,7 +63,7 @@ struct flp_pool {
   int stage_next = 0;
   void* work = nullptr;           // device workspace (LoRA intermediates), grown on demand
   size_t work_cap = 0;
-  std::mutex mu;
+  mutable std::mutex mu;          // guards the free lists, the staging slots and the workspace
 };
 
 // Staging: acquire a slot with room for `bytes` (waits for the slot's previous use),

@@ -13,6 +13,7 @@
 //                       batches.  Two epilogue variants: GATED (gate and up of an MLP in one pass, silu(g) * u stored)
 //                       and LORA (the expand step of the projection's LoRA branch added to the accumulators).
 // fp32 pools: a plain one-thread-per-output kernel (the fp32 workload is tiny).
+#include <atomic>
 #include <hip/hip_runtime.h>
 
 #include <type_traits>
@@ -596,10 +597,10 @@ flp_status flp_launch_gated_gemm(int dtype, const void* x, int64_t ld_x, const v
   const int tiles_n = (N + GT / 2 - 1) / (GT / 2), tiles_m = (M + GT - 1) / GT;
   if (M <= 0 || N < 128 || K <= 0 || !gemm256_fits(M, N, K, ld_x) || (int64_t)tiles_n * tiles_m < 96) return FLP_ENOTSUP;
   if ((lora_gate != nullptr) != (lora_up != nullptr)) return FLP_ENOTSUP;
-  static bool attr_set = false;
-  if (!attr_set) {
+  static std::atomic<bool> attr_set{false};   // pools on different threads share it
+  if (!attr_set.load(std::memory_order_acquire)) {
     FLP_TRY(gemm256_attrs());
-    attr_set = true;
+    attr_set.store(true, std::memory_order_release);
   }
   const int groups_n = (tiles_n + 3) / 4, groups_m = (tiles_m + 7) / 8;
   const int n_groups = (groups_n * groups_m + 7) / 8 * 8;
@@ -667,10 +668,10 @@ flp_status flp_launch_base_gemm(int dtype, const void* x, int64_t ld_x, const vo
     const int groups_n = (tiles_n + 3) / 4, groups_m = (tiles_m + 7) / 8;
     const int n_groups = (groups_n * groups_m + 7) / 8 * 8;
     dim3 grid256((unsigned)(n_groups * 32));
-    static bool attr_set = false;
-    if (!attr_set) {
+    static std::atomic<bool> attr_set{false};   // pools on different threads share it
+    if (!attr_set.load(std::memory_order_acquire)) {
       FLP_TRY(gemm256_attrs());
-      attr_set = true;
+      attr_set.store(true, std::memory_order_release);
     }
     const uint16_t* none = nullptr;
     if (lora && dtype == FLP_F16)

@@ -4,6 +4,7 @@
 //
 // This file holds the adapter segmentation (stable counting sort of token indices by
 // adapter id) and the vector-ALU shrink / expand kernels that serve fp32 pools.
+#include <atomic>
 #include <hip/hip_runtime.h>
 
 #include "flp_internal.h"
@@ -471,11 +472,11 @@ flp_status flp_launch_lora_segment(int32_t T, const int32_t* token_adapter, int3
                                    int32_t* tile_start, int32_t tg, int32_t* group_start, hipStream_t stream,
                                    int32_t* inv_perm, int32_t* vrow_base) {
   const size_t smem = ((size_t)(kSegWaves + 2) * (size_t)(n_adapters > 0 ? n_adapters : 1) + 4 * kSegWaves + 4) * 4;
-  static bool attr_set = false;
-  if (!attr_set) {
+  static std::atomic<bool> attr_set{false};   // pools on different threads share it
+  if (!attr_set.load(std::memory_order_acquire)) {
     FLP_TRY_HIP(hipFuncSetAttribute((const void*)lora_segment_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
                                     160 * 1024));
-    attr_set = true;
+    attr_set.store(true, std::memory_order_release);
   }
   hipLaunchKernelGGL(lora_segment_kernel, dim3(1), dim3(1024), smem, stream, T, token_adapter, n_adapters, n_seg,
                      seg_adapter, seg_start, perm, tm, tile_start, tg, group_start, inv_perm, vrow_base);

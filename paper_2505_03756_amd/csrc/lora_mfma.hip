@@ -18,6 +18,7 @@
 //           B coefficients are fed to both halves).  Two column tiles are interleaved so
 //           that a lane ends up with 8 consecutive columns of one token: y is read and
 //           written in 16-byte pieces.
+#include <atomic>
 #include <hip/hip_runtime.h>
 
 #include "flp_internal.h"
@@ -777,11 +778,11 @@ flp_status launch_pair(const FlpLoraArgs& a, const FlpLoraMfma& c, hipStream_t s
   constexpr bool ONEP = NT >= 2;                       // one projection per workgroup from rank 17 on
   const int n_pl = ONEP ? 1 : a.n_proj;
   const size_t smem = (size_t)4 * MT * n_pl * NT * 4 * 64 * sizeof(float);
-  static bool attr_set = false;
-  if (!attr_set) {
+  static std::atomic<bool> attr_set{false};   // pools on different threads share it
+  if (!attr_set.load(std::memory_order_acquire)) {
     FLP_TRY_HIP(hipFuncSetAttribute((const void*)lora_shrink_mfma_kernel<L, MT, NT, ONEP>,
                                     hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));
-    attr_set = true;
+    attr_set.store(true, std::memory_order_release);
   }
   bool staged = false;
   if constexpr (NT >= 2 && MT == 2) {

@@ -140,6 +140,7 @@ extern "C" flp_status flp_pool_destroy(flp_pool* p) {
 extern "C" int64_t flp_pool_block_bytes(const flp_pool* p) { return p ? p->block_bytes : 0; }
 extern "C" int64_t flp_pool_num_free(const flp_pool* p, int32_t tier) {
   if (!p || tier < 0 || tier > 1) return -1;
+  std::lock_guard<std::mutex> lk(p->mu);               // another thread may be allocating
   return (int64_t)p->tier[tier].stack.size();
 }
 extern "C" void* flp_pool_base(const flp_pool* p, int32_t tier) {
