@@ -67,6 +67,7 @@ class Cache:
         h = C.c_void_p()
         flpool._check(L.flc_create(pool._h, C.byref(cfg), C.byref(h)))
         self._h = h
+        pool._dependents.add(self)             # closing the pool closes this cache first
         self._cap = 0
         self._grow(4096)
 

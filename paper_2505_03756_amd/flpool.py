@@ -10,6 +10,7 @@ from __future__ import annotations
 
 import ctypes as C
 import os
+import weakref
 from typing import Optional, Sequence
 
 import numpy as np
@@ -137,11 +138,14 @@ class Pool:
         h = C.c_void_p()
         _check(self._lib.flp_pool_create(C.byref(cfg), C.byref(h)))
         self._h = h
+        self._dependents = weakref.WeakSet()   # objects created on this pool that must be closed before it
         self.block_bytes = int(self._lib.flp_pool_block_bytes(h))
         self.block_elems = 2 * block_tokens * n_kv_heads * head_dim
 
     def close(self):
         if getattr(self, "_h", None):
+            for d in list(getattr(self, "_dependents", ())):   # a cache hands its blocks back to the pool it is closed on
+                d.close()
             self._lib.flp_pool_destroy(self._h)
             self._h = None
 

@@ -256,3 +256,21 @@ def test_random_walk_over_the_host_abi_under_sanitizers(tmp_path):
     r = subprocess.run([exe, "3000"], capture_output=True, text=True, timeout=300, env=env)
     assert r.returncode == 0, (r.stdout + r.stderr)[-3000:]
     assert "accounting held after every call" in r.stdout
+
+
+def test_closing_the_pool_first_closes_its_caches():
+    """flc_destroy returns the nodes' blocks to the pool, so the pool must outlive the cache: the binding closes
+    the caches of a pool before the pool itself, whatever order the caller (or the garbage collector) picks."""
+    pool = host_pool(16, 16, 4)
+    c = flcache.Cache(pool, 4)
+    c.add_lora(1, 3, 0, 0.0)
+    assert pool.num_free(0) == 13
+    pool.close()
+    assert c._h is None and pool._h is None
+    c.close()                                   # a second time: nothing left to do
+    pool2 = host_pool(16, 16, 4)
+    c2 = flcache.Cache(pool2, 4)
+    c2.add_lora(1, 3, 0, 0.0)
+    c2.close()
+    assert pool2.num_free(0) == 16              # the LoRA's blocks came back
+    pool2.close()
