@@ -160,7 +160,12 @@ flp_status flp_paged_prefix_attention(flp_pool* pool, const flp_attn_batch* batc
  * error; its row is left at the base term.  The projections of one batch share
  * x (q, k and v read it once).  The call keeps its intermediates (segment lists,
  * fp32 x.A^T) in a workspace owned by the pool: LoRA calls on one pool must be
- * ordered with respect to each other (same stream, or events between them). */
+ * ordered with respect to each other (same stream, or events between them).
+ * Limits, checked on the host before anything is enqueued: n_adapters <= 2048
+ * and 1 <= max_rank <= 64 (FLP_ERANGE otherwise).  rank[] lives in device memory
+ * and is not read by the host: rank[a] > max_rank is a caller error, and every
+ * kernel then uses the first max_rank page-rows of that adapter's A and B
+ * (the same result whatever the batch size). */
 #define FLP_MAX_PROJ 4
 
 typedef struct {
@@ -181,8 +186,8 @@ typedef struct {
   int32_t n_tokens;
   int32_t d_in;
   int64_t ld_x;                   /* elements between rows of x (>= d_in)                     */
-  int32_t n_adapters;
-  int32_t max_rank;               /* upper bound of rank[] (<= 64)                            */
+  int32_t n_adapters;             /* <= 2048                                                  */
+  int32_t max_rank;               /* upper bound of rank[], 1..64                             */
   int32_t n_proj;                 /* 1..FLP_MAX_PROJ                                          */
   int32_t reserved;
   const void*    x;               /* device [T, ld_x], pool dtype                             */
@@ -202,7 +207,7 @@ flp_status flp_lora_apply_paged(flp_pool* pool, const flp_lora_batch* batch, voi
  * seg_start[n_adapters+1] (offsets into perm; seg_start[n_seg] = number of
  * tokens with an adapter); perm[n_tokens] (token indices grouped by adapter,
  * original order kept inside a group).  Entries past the counts are
- * unspecified.  n_adapters <= 4096. */
+ * unspecified.  n_adapters <= 2048 (FLP_ERANGE otherwise). */
 flp_status flp_lora_segment(flp_pool* pool, int32_t n_tokens, const int32_t* token_adapter, int32_t n_adapters,
                             int32_t* n_seg, int32_t* seg_adapter, int32_t* seg_start, int32_t* perm,
                             void* hip_stream);

@@ -103,10 +103,15 @@ constexpr int kWaitVm0 = 0 | (7 << 4) | (15 << 8);
 // Written as inline assembly on purpose: the compiler does not see these loads, so it neither
 // counts them in its own memory-counter waits nor makes every later LDS read wait for all of
 // them; the kernel orders them against the LDS reads itself (s_waitcnt vmcnt + barrier).
+// M0 is named as clobbered so that no pass keeps a value of its own alive in it across the statement; the
+// compiler notes that it reserves the register, which is the point.
+#pragma clang diagnostic push
+#pragma clang diagnostic ignored "-Winline-asm"
 __device__ __forceinline__ void load_to_lds16(const void* base, uint32_t voff, uint32_t lds) {
   asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(voff), "s"(base), "s"(lds)
-               : "memory");
+               : "memory", "m0");
 }
+#pragma clang diagnostic pop
 typedef __attribute__((address_space(3))) uint8_t lds_u8;
 typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
 

@@ -210,10 +210,15 @@ constexpr int GT = 256, GK = 64, kGOperand = GT * GK * 2, kGStage = 2 * kGOperan
 // s_waitcnt immediate (gfx9 encoding: vmcnt[3:0] + [15:14], expcnt[6:4], lgkmcnt[11:8]): vmcnt only
 constexpr int vmcnt_imm(int n) { return (n & 15) | ((n >> 4) << 14) | (7 << 4) | (15 << 8); }
 
+// M0 is named as clobbered so that no pass keeps a value of its own alive in it across the statement; the
+// compiler notes that it reserves the register, which is the point.
+#pragma clang diagnostic push
+#pragma clang diagnostic ignored "-Winline-asm"
 __device__ __forceinline__ void gload_lds16(const void* base, uint32_t voff, uint32_t lds) {
   asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(voff), "s"(base), "s"(lds)
-               : "memory");
+               : "memory", "m0");
 }
+#pragma clang diagnostic pop
 typedef __attribute__((address_space(3))) uint8_t g_lds_u8;
 
 // swizzle of row r: the 16-byte chunk c of the row sits in slot c ^ gswz(r) of the row's 128 bytes

@@ -101,7 +101,7 @@ __global__ __launch_bounds__(256) void lora_shrink_mfma_kernel(FlpLoraArgs a, Fl
   if (tile >= n_tiles) break;
   const int s = find_segment(a.tile_start, n_seg, tile);
   const int ad = a.seg_adapter[s];
-  const int r = a.rank[ad] < 16 * NT ? a.rank[ad] : 16 * NT;
+  const int r = a.rank[ad] < a.max_rank ? a.rank[ad] : a.max_rank;
   const int TM = 16 * MT;
   const int pos0 = a.seg_start[s] + (tile - a.tile_start[s]) * TM;
   const int pos_end = a.seg_start[s + 1];
@@ -198,9 +198,14 @@ __global__ __launch_bounds__(256) void lora_shrink_mfma_kernel(FlpLoraArgs a, Fl
 // no reduction across waves is needed.  Ranks past the adapter's rank read the adapter's first row: their v
 // entries are finite and meet zero coefficients in the expand kernel.
 typedef __attribute__((address_space(3))) uint8_t l_lds_u8;
+// M0 is named as clobbered so that no pass keeps a value of its own alive in it across the statement; the
+// compiler notes that it reserves the register, which is the point.
+#pragma clang diagnostic push
+#pragma clang diagnostic ignored "-Winline-asm"
 __device__ __forceinline__ void lload_lds16(uint64_t addr, uint32_t lds) {
-  asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(addr), "s"(lds) : "memory");
+  asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(addr), "s"(lds) : "memory", "m0");
 }
+#pragma clang diagnostic pop
 constexpr int lvmcnt(int n) { return (n & 15) | ((n >> 4) << 14) | (7 << 4) | (15 << 8); }   // s_waitcnt vmcnt(n) only
 
 template <typename L, int NT, int NPJ>
@@ -241,7 +246,7 @@ __global__ __launch_bounds__(256) void lora_shrink_lds_kernel(FlpLoraArgs a, Flp
     if (XT == 4 && ((tile - a.tile_start[s]) & 1)) continue;     // the second tile of a pair: its neighbour does it
     const bool second = XT == 4 && tile + 1 < a.tile_start[s + 1];  // the pair is complete
     const int ad = a.seg_adapter[s];
-    const int r = a.rank[ad] < 16 * NT ? a.rank[ad] : 16 * NT;
+    const int r = a.rank[ad] < a.max_rank ? a.rank[ad] : a.max_rank;
     const int pos0 = a.seg_start[s] + (tile - a.tile_start[s]) * 32;
     const int pos_end = a.seg_start[s + 1];
     const int kbeg = ks * c.k_per_split;
@@ -360,7 +365,7 @@ __global__ __launch_bounds__(256) void lora_shrink_lds16_kernel(FlpLoraArgs a, F
     if (tile >= n_tiles) break;
     const int s = find_segment(a.tile_start, n_seg, tile);
     const int ad = a.seg_adapter[s];
-    const int r = a.rank[ad] < 16 ? a.rank[ad] : 16;
+    const int r = a.rank[ad] < a.max_rank ? a.rank[ad] : a.max_rank;
     const int pos0 = a.seg_start[s] + (tile - a.tile_start[s]) * 32;
     const int pos_end = a.seg_start[s + 1];
     const int kbeg = ks * c.k_per_split;
@@ -481,7 +486,7 @@ __global__ __launch_bounds__(64) void lora_expand_mfma_kernel(FlpLoraArgs a, Flp
   if (slab_begin >= pr.d_out) continue;
   const int s = find_segment(a.group_start, n_seg, group);
   const int ad = a.seg_adapter[s];
-  const int r = a.rank[ad] < 16 * NT ? a.rank[ad] : 16 * NT;
+  const int r = a.rank[ad] < a.max_rank ? a.rank[ad] : a.max_rank;
   if (r <= 0) continue;
   const float sc = a.scale[ad];
   const int RP = 16 * NT, TM = 16 * c.mt;
@@ -653,7 +658,7 @@ __global__ __launch_bounds__(256) void lora_expand_lds_kernel(FlpLoraArgs a, Flp
     if (slab_begin >= pr.d_out) continue;
     const int s = find_segment(a.group_start, n_seg, group);
     const int ad = a.seg_adapter[s];
-    const int r = a.rank[ad] < 16 * NT ? a.rank[ad] : 16 * NT;
+    const int r = a.rank[ad] < a.max_rank ? a.rank[ad] : a.max_rank;
     if (r <= 0) continue;
     const float sc = a.scale[ad];
     const int RP = 16 * NT, TM = 16 * c.mt;

@@ -201,6 +201,26 @@ def test_lora_argument_checks():
         pool.lora_apply_paged(projs=[proj] * 5, **kw)
     assert e.value.code == flpool.FLP_EINVAL
     pool.lora_apply_paged(projs=[proj], **{**kw, "n_tokens": 0})        # empty batch: success
+    # the limits the header states next to the declarations: 1..64 for max_rank, 2048 adapters for both calls
+    for bad_rank in (0, -1, 65):
+        with pytest.raises(flpool.FlpError) as e:
+            pool.lora_apply_paged(projs=[proj], **{**kw, "max_rank": bad_rank})
+        assert e.value.code == flpool.FLP_ERANGE
+    with pytest.raises(flpool.FlpError) as e:
+        pool.lora_apply_paged(projs=[proj], **{**kw, "n_adapters": 2049})
+    assert e.value.code == flpool.FLP_ERANGE and "2048" in str(e.value)
+
+
+def test_header_and_code_state_the_same_adapter_limit():
+    hdr = open(os.path.join(ROOT, "include", "flpool.h")).read()
+    assert "4096" not in hdr.split("flp_lora_segment")[0].split("FLP_MAX_PROJ")[-1]
+    assert hdr.count("n_adapters <= 2048") >= 2
+    lib = flpool.load()
+    import ctypes
+    fake = ctypes.c_void_p(0x1000)
+    pool = _host_pool(n_kv=2, d=64)
+    rc = lib.flp_lora_segment(pool._h, 4, fake, 2049, fake, fake, fake, fake, None)
+    assert rc == flpool.FLP_ERANGE
 
 
 def test_pool_create_rejects_bad_geometry():
