@@ -200,6 +200,28 @@ typedef struct {
 
 flp_status flp_lora_apply_paged(flp_pool* pool, const flp_lora_batch* batch, void* hip_stream);
 
+/* The same call for callers that cannot allocate device memory (code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc): same
+ * arguments, same kernels, same results bit for bit, but the intermediates live
+ * in a fixed array of flp_static_scratch_bytes() bytes (64 MiB) that every GPU
+ * using the library holds from the moment the library's code is loaded there
+ * until the process ends.  The call allocates and frees nothing (no hipMalloc /
+ * hipFree, no pinned memory, no growth).  A batch whose intermediates do not fit
+ * (roughly 4 * n_tokens * n_proj * max_rank bytes rounded up to whole 16-rank
+ * tiles and doubled or quadrupled when the contraction is split, plus 12 bytes
+ * per token; a dense base adds its transposed copy and, outside the large-batch
+ * path, 4 * n_tokens * d_out bytes per projection) is refused with FLP_ENOSPC
+ * before anything is enqueued; the five benchmark workloads' calls without a
+ * dense base need 1-44 MiB.  The pool's device must be the current device
+ * (FLP_EINVAL otherwise).  All calls on one GPU, from whatever pool or thread,
+ * share that GPU's one array, which keeps the previous call's contents (every
+ * kernel writes what it later reads, nothing needs to start at zero): calls
+ * whose work overlaps in time on one GPU race with each other, so keep them on
+ * one stream or order them with events.  The array's address is looked up when
+ * a pool is created on the device (again here if that failed). */
+flp_status flp_lora_apply_paged_static(flp_pool* pool, const flp_lora_batch* batch, void* hip_stream);
+int64_t    flp_static_scratch_bytes(void);
+
 /* Adapter segmentation used by the call above, exposed for inspection: a stable
  * grouping of token indices by adapter id (section 2.1 names the batched kernel
  * "segmented gather"; the grouping itself is this build's).  Device outputs:

@@ -235,11 +235,16 @@ extern "C" flp_status flp_lora_segment(flp_pool* p, int32_t n_tokens, const int3
 }
 
 namespace {
-flp_status lora_apply_impl(flp_pool* p, const flp_lora_batch* b, void* hip_stream, void* gated_out, int64_t ld_gated);
+flp_status lora_apply_impl(flp_pool* p, const flp_lora_batch* b, void* hip_stream, void* gated_out, int64_t ld_gated,
+                           const FlpFixedWorkspace* fixed = nullptr);
 }
 
 extern "C" flp_status flp_lora_apply_paged(flp_pool* p, const flp_lora_batch* b, void* hip_stream) {
   return lora_apply_impl(p, b, hip_stream, nullptr, 0);
+}
+
+flp_status flp_lora_apply_fixed(flp_pool* p, const flp_lora_batch* b, void* hip_stream, const FlpFixedWorkspace& ws) {
+  return lora_apply_impl(p, b, hip_stream, nullptr, 0, &ws);
 }
 
 flp_status flp_lora_apply_gated(flp_pool* p, const flp_lora_batch* b, void* out, int64_t ld_out, void* hip_stream) {
@@ -252,7 +257,10 @@ flp_status flp_lora_apply_gated(flp_pool* p, const flp_lora_batch* b, void* out,
 
 namespace {
 // gated_out != nullptr: two projections (gate, up) whose results are not stored; gated_out = silu(y0) * y1
-flp_status lora_apply_impl(flp_pool* p, const flp_lora_batch* b, void* hip_stream, void* gated_out, int64_t ld_gated) {
+// fixed != nullptr: the intermediates go into the caller-provided buffer and nothing is allocated; a batch that
+// needs more than the buffer holds is refused before anything is enqueued
+flp_status lora_apply_impl(flp_pool* p, const flp_lora_batch* b, void* hip_stream, void* gated_out, int64_t ld_gated,
+                           const FlpFixedWorkspace* fixed) {
   if (!p || !b) {
     flp_set_error("flp_lora_apply_paged: null pool or batch");
     return FLP_EINVAL;
@@ -381,7 +389,17 @@ flp_status lora_apply_impl(flp_pool* p, const flp_lora_batch* b, void* hip_strea
   // token -> position in segment order, adapter -> first row of its tokens in the shrink output
   const size_t inv_bytes = fused ? perm_bytes + (((size_t)b->n_adapters * 4 + 255) & ~(size_t)255) : 0;
   void* ws = nullptr;
-  FLP_TRY(flp_workspace(p, v_bytes + seg_bytes + perm_bytes + wt_bytes + base_total + splitk_bytes + inv_bytes, &ws));
+  const size_t ws_bytes = v_bytes + seg_bytes + perm_bytes + wt_bytes + base_total + splitk_bytes + inv_bytes;
+  if (fixed) {
+    if (ws_bytes > fixed->cap) {
+      flp_set_error("%s: the batch needs %zu bytes of intermediates, the fixed buffer holds %zu (fewer tokens, a lower "
+                    "max_rank or no dense base make it fit)", fixed->who, ws_bytes, fixed->cap);
+      return FLP_ENOSPC;
+    }
+    FLP_TRY(fixed->resolve(p, &ws));
+  } else {
+    FLP_TRY(flp_workspace(p, ws_bytes, &ws));
+  }
   FlpLoraArgs a{};
   a.pool = p->dev_base;
   a.block_elems = p->block_elems;

@@ -74,6 +74,19 @@ flp_status flp_stage_upload(FlpStageSlot* slot, size_t bytes, hipStream_t stream
 flp_status flp_stage_release(FlpStageSlot* slot, hipStream_t stream);
 flp_status flp_workspace(flp_pool* pool, size_t bytes, void** out);
 
+// A workspace of fixed size that the caller of the LoRA path brings along instead of the pool's growing one:
+// `resolve` returns its device address for the pool's device (called only after the size check has passed).
+struct FlpFixedWorkspace {
+  size_t cap;
+  flp_status (*resolve)(flp_pool* pool, void** out);
+  const char* who;
+};
+// flp_lora_apply_paged with its intermediates in `ws` (no allocation, no growth)
+flp_status flp_lora_apply_fixed(flp_pool* pool, const flp_lora_batch* batch, void* hip_stream, const FlpFixedWorkspace& ws);
+// set-up of the file-scope scratch array for the current device (looks its device address up once per device);
+// called when a pool is created, and again by the entry point that uses the array if that first attempt failed
+flp_status flp_static_scratch_setup(int device, void** out);
+
 // ---- kernel launchers (defined in the .hip files) ---------------------------------------
 flp_status flp_launch_copy_blocks(const uint8_t* src_base, uint8_t* dst_base, const int32_t* src_ids_dev,
                                   const int32_t* dst_ids_dev, int32_t n, int64_t block_bytes,

@@ -118,6 +118,9 @@ extern "C" flp_status flp_pool_create(const flp_pool_config* cfg, flp_pool** out
   }
   freelist_init(p->tier[0], cfg->n_dev_blocks);
   freelist_init(p->tier[1], cfg->n_host_blocks);
+  // set-up for the entry point that may not allocate: find this device's copy of its scratch array now, while
+  // allocation is still allowed (a failure is not this call's; that entry point tries again and reports it)
+  if (p->device >= 0 && flp_static_scratch_setup(p->device, nullptr) != FLP_OK) (void)hipGetLastError();
   *out = p;
   return FLP_OK;
 }

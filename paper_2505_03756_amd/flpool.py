@@ -26,7 +26,7 @@ MAX_PROJ = 4
 EXPORTS = ("flp_pool_create", "flp_pool_destroy", "flp_pool_block_bytes", "flp_pool_num_free", "flp_pool_base",
            "flp_pool_alloc", "flp_pool_free", "flp_pool_swap_in", "flp_pool_swap_out", "flp_kv_append",
            "flp_paged_prefix_attention", "flp_lora_apply_paged", "flp_lora_segment", "flp_last_error",
-           "flp_version")
+           "flp_version", "flp_lora_apply_paged_static", "flp_static_scratch_bytes")
 
 
 class FlpError(RuntimeError):
@@ -72,6 +72,13 @@ def load():
     if not os.path.exists(LIB_PATH):
         raise FlpError(FLP_EINVAL, "libflpool.so is not built; run `python -m paper_2505_03756_amd.build` "
                                    "(or __graft_entry__.build()) first")
+    # Device memory and streams come from torch, which ships a HIP runtime of its own: it has to be in the process
+    # before this library is, so that both resolve to the one runtime (loaded the other way round, this library's
+    # HIP calls report that there is no device).
+    try:
+        import torch  # noqa: F401
+    except ImportError:
+        pass
     lib = C.CDLL(LIB_PATH)
     vp, i32, i64 = C.c_void_p, C.c_int32, C.c_int64
     lib.flp_pool_create.argtypes = [C.POINTER(PoolConfig), C.POINTER(vp)]
@@ -90,6 +97,8 @@ def load():
     lib.flp_paged_prefix_attention.argtypes = [vp, C.POINTER(AttnBatch), vp]
     lib.flp_lora_apply_paged.argtypes = [vp, C.POINTER(LoraBatch), vp]
     lib.flp_lora_segment.argtypes = [vp, i32, vp, i32, vp, vp, vp, vp, vp]
+    lib.flp_lora_apply_paged_static.argtypes = [vp, C.POINTER(LoraBatch), vp]
+    lib.flp_static_scratch_bytes.restype = i64
     lib.flp_last_error.restype = C.c_char_p
     lib.flp_version.restype = C.c_char_p
     for name in EXPORTS:
@@ -213,9 +222,10 @@ class Pool:
                                           _ptr(seg_adapter), _ptr(seg_start), _ptr(perm), _stream(stream)))
 
     def lora_apply_paged(self, x, token_adapter, rank, scale, block_tables, projs: Sequence[dict], n_tokens, d_in,
-                         n_adapters, max_rank, ld_x=None, stream=None):
+                         n_adapters, max_rank, ld_x=None, stream=None, static=False):
         """projs: dicts with y, d_out, a_tab_off, a_row_base, b_tab_off, b_row_base and optional ld_y, w_base, w_base_layout
-        (0: w_base is [d_in, d_out]; 1: [d_out, d_in])."""
+        (0: w_base is [d_in, d_out]; 1: [d_out, d_in]).  static=True calls flp_lora_apply_paged_static (same
+        arguments, intermediates in the library's fixed scratch array, nothing allocated)."""
         if not 1 <= len(projs) <= MAX_PROJ:
             raise FlpError(FLP_EINVAL, "1..%d projections per call" % MAX_PROJ)
         b = LoraBatch()
@@ -231,7 +241,12 @@ class Pool:
             pr.w_base_layout = int(p.get("w_base_layout", 0))
             pr.a_tab_off, pr.a_row_base = _ptr(p["a_tab_off"]), _ptr(p["a_row_base"])
             pr.b_tab_off, pr.b_row_base = _ptr(p["b_tab_off"]), _ptr(p["b_row_base"])
-        _check(self._lib.flp_lora_apply_paged(self._h, C.byref(b), _stream(stream)))
+        fn = self._lib.flp_lora_apply_paged_static if static else self._lib.flp_lora_apply_paged
+        _check(fn(self._h, C.byref(b), _stream(stream)))
+
+
+def static_scratch_bytes():
+    return int(load().flp_static_scratch_bytes())
 
 
 def version():

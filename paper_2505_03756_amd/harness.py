@@ -96,9 +96,10 @@ class GpuStep:
         self.torch.cuda.synchronize()
         return to_np(self.host, self.sd)
 
-    def lora(self, names, x_key="x", w_base=None):
+    def lora(self, names, x_key="x", w_base=None, static=False):
         """Run flp_lora_apply_paged for the named projections on copies of the base terms; returns storage arrays.
-        `w_base`: optional dict name -> device tensor [d_in, d_out]; y then starts as garbage and is overwritten."""
+        `w_base`: optional dict name -> device tensor [d_in, d_out]; y then starts as garbage and is overwritten.
+        `static`: call flp_lora_apply_paged_static instead (intermediates in the library's fixed scratch array)."""
         st = self.step
         ys = {n: self.acts["base_" + n].clone() for n in names}
         projs = [dict(y=ys[n], d_out=st.proj[n].d_out, **self.proj[n]) for n in names]
@@ -108,7 +109,7 @@ class GpuStep:
         x = self.acts[x_key]
         self.pool.lora_apply_paged(x, self.token_adapter, self.rank, self.scale, self.lora_tables, projs,
                                    n_tokens=st.n_tokens, d_in=x.shape[1], n_adapters=len(st.rank),
-                                   max_rank=int(max(1, st.rank.max())))
+                                   max_rank=int(max(1, st.rank.max())), static=static)
         self.torch.cuda.synchronize()
         return {n: to_np(ys[n], self.sd) for n in names}
 

@@ -211,6 +211,19 @@ def test_lora_argument_checks():
     assert e.value.code == flpool.FLP_ERANGE and "2048" in str(e.value)
 
 
+def test_static_lora_entry_point_refuses_oversized_batches_on_the_host():
+    """The entry point that allocates nothing checks the batch against its fixed 64 MiB before it touches the GPU."""
+    pool = _host_pool(n_kv=8, d=128)           # block = 32768 elements
+    fake = 0x1000
+    proj = dict(y=fake, d_out=16384, w_base=fake, a_tab_off=fake, a_row_base=fake, b_tab_off=fake, b_row_base=fake)
+    kw = dict(x=fake, token_adapter=fake, rank=fake, scale=fake, block_tables=fake, n_tokens=1000, d_in=16384,
+              n_adapters=2, max_rank=8, stream=0)
+    assert flpool.static_scratch_bytes() == 64 << 20
+    with pytest.raises(flpool.FlpError) as e:
+        pool.lora_apply_paged(projs=[proj], static=True, **kw)
+    assert e.value.code == flpool.FLP_ENOSPC and "fixed buffer" in str(e.value)
+
+
 def test_header_and_code_state_the_same_adapter_limit():
     hdr = open(os.path.join(ROOT, "include", "flpool.h")).read()
     assert "4096" not in hdr.split("flp_lora_segment")[0].split("FLP_MAX_PROJ")[-1]
