@@ -94,6 +94,9 @@ class LayerConfig:
     lora_std: float = 0.02
     seed: int = 20250503
     skew_std: float = 32.0          # standard deviation, in adapter ids, of the "skewed" distribution
+    share_frac: float = 0.0         # probability that a sequence shares leading prefix blocks with an earlier
+                                    # sequence of the same adapter (paper section 4.1: queries of one LoRA that
+                                    # start alike hang below the same nodes; KV of different LoRAs is never shared)
 
     @property
     def block_elems(self) -> int:
@@ -332,10 +335,28 @@ def make_step(cfg: LayerConfig, seed: Optional[int] = None,
     kv_tables = np.full((S, max_blocks), -1, dtype=np.int32)
     pre_ids: List[np.ndarray] = []
     fresh_ids: List[np.ndarray] = []
+    # shared prefixes: a sequence may reuse the physical blocks of the leading FULL prefix blocks of an earlier
+    # sequence with the same adapter (a random number of them, at least one); the block that its own new tokens
+    # continue in is never shared.  Drawn only when the knob is on, so other workloads keep their streams.
+    n_shared = np.zeros(S, dtype=np.int64)
+    donor = np.full(S, -1, dtype=np.int64)
+    if cfg.share_frac > 0:
+        last_of: Dict[int, int] = {}
+        for i in range(S):
+            a = int(seq_adapter[i])
+            j = last_of.get(a, -1)
+            if j >= 0 and rng.random() < cfg.share_frac:
+                room = min(int(prefix_len[i]) // bt, int(prefix_len[j]) // bt)
+                if room > 0:
+                    n_shared[i] = int(rng.integers(1, room + 1))
+                    donor[i] = j
+            last_of[a] = i
     for i in range(S):
-        ids = np.asarray(alloc_dev(int(nblk[i])), dtype=np.int32)
+        ns = int(n_shared[i])
+        own = np.asarray(alloc_dev(int(nblk[i]) - ns), dtype=np.int32)
+        ids = np.concatenate([kv_tables[donor[i], :ns], own]).astype(np.int32) if ns else own
         kv_tables[i, :len(ids)] = ids
-        pre_ids.append(ids[:int(npre[i])])
+        pre_ids.append(ids[ns:int(npre[i])])
         fresh_ids.append(ids[int(npre[i]):])
     prefix_block_ids = np.concatenate(pre_ids).astype(np.int32)
     fresh_block_ids = np.concatenate(fresh_ids).astype(np.int32)

@@ -11,26 +11,70 @@ from paper_2505_03756_amd import workload as wl
 pytestmark = pytest.mark.gpu
 
 
-def _run_case(cfg, n_sample_tokens, seed=None):
+def _blocks_that_fit(cfg, candidates, headroom_gib):
+    """Largest device block count of `candidates` that the card holds beside `headroom_gib` of activations,
+    workspace and comparison copies."""
+    import gc
     import torch
+    gc.collect()
+    torch.cuda.synchronize()
+    torch.cuda.empty_cache()                      # earlier cases' pools sit in torch's cache
+    free, total = torch.cuda.mem_get_info()
+    print("\n[full size %s] card: %.1f GiB free of %.1f" % (cfg.name, free / 2 ** 30, total / 2 ** 30), flush=True)
+    for n in candidates:
+        if n * cfg.block_bytes + headroom_gib * 2 ** 30 <= free:
+            return n
+    pytest.skip("the card has %.0f GiB free: not enough for the smallest pool of this case" % (free / 2 ** 30))
+
+
+def _rows_equal(gp, ids, want, what):
+    """Device blocks `ids` against the rows of `want`, byte for byte, a few thousand blocks at a time."""
+    for lo in range(0, len(ids), 4096):
+        got = gp.rows(ids[lo:lo + 4096])
+        assert np.array_equal(got.view(np.uint8), want[lo:lo + 4096].view(np.uint8)), "%s (blocks %d..)" % (what, lo)
+
+
+def _seq_sample(step, rng, n):
+    """n sequences: the longest context, the last one (its rows end the batch), the first, the rest at random."""
+    S = len(step.prefix_len)
+    must = {int(np.argmax(step.prefix_len + step.new_len)), S - 1, 0}
+    rest = [int(i) for i in rng.permutation(S) if int(i) not in must]
+    return sorted(must | set(rest[:max(0, n - len(must))]))
+
+
+def _run_case(cfg, n_lora_rows, n_dense_seqs, n_row_seqs=None, cells_per_seq=None, seed=None):
+    """The whole batch on the GPU, in the launch configuration bench.py times.  Integer and byte results are compared
+    in full.  Floating point: the LoRA rows of a sample stratified over the adapters' segments and tiles; the
+    attention rows of a sample stratified over the row tiles, their waves, the ragged last tile and the 64-key tile
+    boundaries (per-row C oracle), and EVERY output element of `n_dense_seqs` whole sequences (the whole-sequence
+    form of the oracle)."""
+    import time
+    import torch
+    from oracle.attention_dense import paged_attention_sequence
+    from helpers import attention_rows_sample, lora_rows_sample
+    t_start = time.time()
     step = wl.make_step(cfg, seed=seed)
-    T = step.n_tokens
+    T, S = step.n_tokens, cfg.n_seqs
+    print("\n[full size %s] T=%d S=%d blocks=%d pool=%d x %d KiB (%.0f s to draw)" % (
+        cfg.name, T, S, len(step.content_ids), cfg.n_dev_blocks, cfg.block_bytes >> 10, time.time() - t_start), flush=True)
     rng = np.random.default_rng(12345)
     rtol, atol = TOL[cfg.dtype]
     gp = SparseGpuPool(step)
     g = GpuStep(step, gpool=gp)
     pool_c, kv_c, lt_c = compact_step(step)             # what the device tier must hold after the swap-in
     bt, n_kv, d, n_h = cfg.block_tokens, cfg.n_kv_heads, cfg.head_dim, cfg.n_q_heads
+    sdt = np.uint16 if cfg.dtype != "f32" else np.float32
 
     # ---- swap: out first, then in; every touched block bit-exact afterwards
     out_before = gp.rows(step.swap_out_dev) if len(step.swap_out_dev) else None
     g.pool.swap_out(step.swap_out_dev, step.swap_out_host)
     g.pool.swap_in(step.swap_in_host, step.swap_in_dev)
-    assert np.array_equal(gp.rows(step.content_ids).view(np.uint8), pool_c.view(np.uint8)), "swap-in"
+    _rows_equal(gp, step.content_ids, pool_c, "swap-in")
     if out_before is not None:
         torch.cuda.synchronize()
-        host_rows = gp.host.numpy()[step.swap_out_host].view(np.uint16 if cfg.dtype != "f32" else np.float32)
+        host_rows = gp.host.numpy()[step.swap_out_host].view(sdt)
         assert np.array_equal(host_rows.view(np.uint8), out_before.view(np.uint8)), "swap-out"
+        del out_before, host_rows
 
     # ---- segmentation of the full batch, bit-exact
     n_ad = len(step.rank)
@@ -45,8 +89,9 @@ def _run_case(cfg, n_sample_tokens, seed=None):
     assert np.array_equal(d_sa.cpu().numpy()[:n], seg_adapter) and np.array_equal(d_ss.cpu().numpy()[:n + 1], seg_start)
     assert np.array_equal(d_perm.cpu().numpy()[:seg_start[n]], perm)
 
-    # ---- LoRA: all projections at full size, sampled rows against the oracle
-    sel = np.sort(rng.choice(T, size=min(T, n_sample_tokens), replace=False)).astype(np.int32)
+    # ---- LoRA: all projections at full size; the sampled rows against the oracle
+    sel = lora_rows_sample(step, rng, n_lora_rows) if n_lora_rows < T else np.arange(T, dtype=np.int32)
+    assert len(sel) >= min(T, n_lora_rows)
     groups = {}
     for p in cfg.projections:
         groups.setdefault(step.proj[p].d_in, []).append(p)
@@ -64,56 +109,80 @@ def _run_case(cfg, n_sample_tokens, seed=None):
                 assert ok, "LoRA %s: max err %g (%d bad)" % (nme, worst, nbad)
                 base = wl.dequantize(step.acts["base_" + nme][sel], cfg.dtype)
                 assert np.abs(want - base).max() > 10 * atol, "sample carries no delta"
+                # the delta itself at one spacing of the element type at the output's magnitude
+                ulp = 2.0 ** (-10 if cfg.dtype == "f16" else -7)
+                err = np.abs((wl.dequantize(got[nme][sel], cfg.dtype) - base) - (want - base))
+                assert err.max() <= ulp * (np.abs(want).max() + 1.0), (nme, err.max())
+            del got
+    print("[full size %s] LoRA rows checked: %d (%.0f s)" % (cfg.name, len(sel), time.time() - t_start), flush=True)
 
     # ---- KV append, bit-exact on every touched block
     g.pool.kv_append(g.acts["k_new"], g.acts["v_new"], step.cu_new, step.prefix_len, g.kv_tables)
     oracle.kv_append(pool_c, cfg.dtype, bt, n_kv, d, step.cu_new, step.prefix_len, kv_c, step.acts["k_new"],
                      step.acts["v_new"])
-    assert np.array_equal(gp.rows(step.content_ids).view(np.uint8), pool_c.view(np.uint8)), "append"
+    _rows_equal(gp, step.content_ids, pool_c, "append")
 
-    # ---- attention at full size, sampled tokens (all heads) against the oracle
+    # ---- attention at full size
     q = g.acts["q"]
     out = torch.zeros_like(q)
     g.pool.paged_prefix_attention(q, out, step.cu_new, step.prefix_len, g.kv_tables, n_h)
     torch.cuda.synchronize()
-    # favour the ends of sequences (longest contexts, tile tails) and their starts (prefix seam)
-    ends = step.cu_new[1:] - 1
-    starts = step.cu_new[:-1]
-    pick = np.unique(np.concatenate([rng.choice(ends, size=min(len(ends), n_sample_tokens // 3), replace=False),
-                                     rng.choice(starts, size=min(len(starts), n_sample_tokens // 3), replace=False),
-                                     sel[:n_sample_tokens // 3]])).astype(np.int32)
-    got = wl.dequantize(out[torch.from_numpy(pick.astype(np.int64)).cuda()].cpu().numpy().view(
-        np.uint16 if cfg.dtype != "f32" else np.float32), cfg.dtype).reshape(len(pick), n_h, d)
-    want = oracle.paged_attention(pool_c, cfg.dtype, bt, n_kv, d, n_h, step.cu_new, step.prefix_len, kv_c,
-                                  step.acts["q"], sel=pick)
-    ok, worst, nbad = close(got, want, rtol, atol)
-    assert ok, "attention: max err %g (%d bad)" % (worst, nbad)
     # property that holds at any size: every output row is finite (no poisoned slot leaked in)
     assert bool(torch.isfinite(out.view(torch.float16 if cfg.dtype == "f16" else torch.bfloat16)).all())
+    out_np = wl.dequantize(out.cpu().numpy().view(sdt), cfg.dtype).reshape(T, n_h, d)
+    # (a) rows stratified over the kernel's structure, one by one
+    row_seqs = None if n_row_seqs is None else _seq_sample(step, rng, n_row_seqs)
+    pick = attention_rows_sample(step, rng, cells_per_seq=cells_per_seq, seqs=row_seqs)
+    want = oracle.paged_attention(pool_c, cfg.dtype, bt, n_kv, d, n_h, step.cu_new, step.prefix_len, kv_c,
+                                  step.acts["q"], sel=pick)
+    ok, worst, nbad = close(out_np[pick], want, rtol, atol)
+    assert ok, "attention rows: max err %g (%d bad)" % (worst, nbad)
+    print("[full size %s] attention rows checked one by one: %d (%.0f s)" % (cfg.name, len(pick), time.time() - t_start),
+          flush=True)
+    # (b) whole sequences, every output element
+    seqs = _seq_sample(step, rng, n_dense_seqs)
+    n_rows = 0
+    for i in seqs:
+        lo, hi = int(step.cu_new[i]), int(step.cu_new[i + 1])
+        want = paged_attention_sequence(pool_c, cfg.dtype, bt, n_kv, d, n_h, step.cu_new, step.prefix_len, kv_c,
+                                        step.acts["q"], i)
+        ok, worst, nbad = close(out_np[lo:hi], want, rtol, atol)
+        assert ok, "attention, sequence %d (P=%d, N=%d): max err %g (%d bad)" % (
+            i, step.prefix_len[i], hi - lo, worst, nbad)
+        n_rows += hi - lo
+    print("[full size %s] whole sequences checked: %d (%d rows) (%.0f s)" % (cfg.name, len(seqs), n_rows,
+                                                                            time.time() - t_start), flush=True)
     gp.pool.close()
 
 
 def test_7b_prefill_full_size():
-    """Config 1 of the benchmark list (the one bench.py times): fp16, 64 prefill sequences, 40 % swap-in."""
-    _run_case(wl.config("7b_prefill"), n_sample_tokens=48)
+    """Config 1 of the benchmark list: fp16, 64 prefill sequences, 40 % swap-in.  All 18 953 LoRA rows, about 1600
+    stratified attention rows one by one, and every output element of all 64 sequences."""
+    _run_case(wl.config("7b_prefill"), n_lora_rows=1 << 30, n_dense_seqs=64)
 
 
 def test_7b_decode_full_size():
-    """Config 2: bf16 decode, 256 sequences of 512-4096 context, 100 adapters of mixed rank."""
-    _run_case(wl.config("7b_decode").scaled(n_dev_blocks=40000), n_sample_tokens=48)
+    """Config 2: bf16 decode, 256 sequences of 512-4096 context, 100 adapters of mixed rank: every row of the batch."""
+    _run_case(wl.config("7b_decode").scaled(n_dev_blocks=40000), n_lora_rows=1 << 30, n_dense_seqs=32)
 
 
-def test_13b_shapes_in_full_size_pool():
-    """Config 3 shapes (hidden 5120, 40 heads, MLP 13824, rank 32 on seven projections, Zipf 1.2) on a
-    seeded subsample of 32 sequences, in a device tier of the full 600 000 x 320 KiB (197 GB), so that
-    64-bit block offsets and page-rows that do not divide the block are exercised at real addresses."""
-    _run_case(wl.config("13b").scaled(n_seqs=32, n_host_blocks=4096), n_sample_tokens=36)
+def test_13b_full_batch_in_full_size_pool():
+    """Config 3 (hidden 5120, 40 heads, MLP 13824, rank 32 on seven projections, Zipf 1.2, 25 % swapped in and
+    out): all 128 sequences on the GPU in a device tier of the full 600 000 x 320 KiB (197 GB), so that 64-bit
+    block offsets and page-rows that do not divide the block are exercised at real addresses."""
+    cfg = wl.config("13b")
+    _run_case(cfg.scaled(n_dev_blocks=_blocks_that_fit(cfg, (600000, 500000, 400000), 40), n_host_blocks=16384),
+              n_lora_rows=1024, n_dense_seqs=32, n_row_seqs=32)
 
 
-def test_34b_gqa_shapes_in_full_size_pool():
-    """Config 4 shapes (hidden 8192, 64 query / 8 kv heads, rank 64, prefixes up to 16384, 75 % decode) on a
-    seeded subsample of 64 sequences, in a device tier of 3 000 000 x 64 KiB (197 GB)."""
-    _run_case(wl.config("34b_gqa").scaled(n_seqs=64, n_dev_blocks=3000000, n_host_blocks=8192), n_sample_tokens=36)
+def test_34b_gqa_full_batch_in_the_largest_pool():
+    """Config 4 (hidden 8192, 64 query / 8 kv heads, rank 64, prefixes up to 16384, 75 % decode): all 512 sequences
+    on the GPU, in the largest device tier of 64 KiB blocks that the card holds (3 750 000 = 246 GB named by the
+    workload; fewer if the card's free memory says so)."""
+    cfg = wl.config("34b_gqa")
+    _run_case(cfg.scaled(n_dev_blocks=_blocks_that_fit(cfg, (3750000, 3500000, 3250000, 3000000), 36),
+                         n_host_blocks=65536),
+              n_lora_rows=1024, n_dense_seqs=32, n_row_seqs=64, cells_per_seq=0)
 
 
 def test_7b_prefill_dense_base_full_size():

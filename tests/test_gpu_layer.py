@@ -150,6 +150,11 @@ LAYER_CASES = {
     "bf16_all_lora_inside_gemm": lambda: layer_cfg("bf16", hidden=2048, n_q_heads=16, n_kv_heads=16, n_seqs=24,
                                                    prefix_range=(0, 200), new_range=(125, 150), mlp_dim=3136,
                                                    n_dev_blocks=3500, ranks=(8, 16, 32), seed=50),
+    # the same in fp16, where the composed layer's bound (8 spacings) is 7.8e-3: tight enough that a missing rank-8
+    # branch on gate or up (delta of standard deviation ~0.03 before the down projection) cannot pass
+    "f16_all_lora_inside_gemm": lambda: layer_cfg("f16", hidden=2048, n_q_heads=16, n_kv_heads=16, n_seqs=24,
+                                                  prefix_range=(0, 200), new_range=(125, 150), mlp_dim=3136,
+                                                  n_dev_blocks=3500, ranks=(8, 16, 32), seed=51),
     "bf16_fused_gate_up": lambda: layer_cfg("bf16", projections=("q", "k", "v", "o"), n_seqs=10, prefix_range=(0, 300),
                                             new_range=(110, 160), mlp_dim=3136, n_dev_blocks=2500, seed=48),
 }

@@ -415,3 +415,88 @@ def test_lora_no_adapter_tokens_and_zero_b():
                                   np.zeros(pr.d_out, np.uint16))
     g2 = GpuStep(step, zero, np.zeros((1, cfg.block_elems), dev0.dtype))
     assert np.array_equal(g2.lora(["q"])["q"], step.acts["base_q"])
+
+
+@pytest.mark.parametrize("with_base", [False, True])
+@pytest.mark.parametrize("dtype,ranks", [("f16", (16,)), ("bf16", (32,)), ("f16", (64,)), ("bf16", (8, 16, 32, 64))])
+def test_lora_adapters_drawn_per_token(dtype, ranks, with_base):
+    """Every token draws its adapter on its own (12 adapters and "none"), so a 32-token tile of the sorted batch, a
+    256-token tile group and the 128 tokens of a GEMM wave all mix adapters, segments end inside tiles, and rows
+    without an adapter sit between the others: on the tiled path (2816 tokens and more), without a dense base
+    (shrink and expand kernels) and with one (the LoRA branch inside the large-batch GEMM), at one, two and four
+    rank tiles and with mixed ranks."""
+    cfg = small_cfg(dtype, hidden=512, n_q_heads=18, n_kv_heads=18, n_seqs=24, prefix_range=(0, 0),
+                    new_range=(118, 160), n_adapters=12, ranks=ranks, adapter_dist="distinct", n_dev_blocks=2400,
+                    swap_in_frac=0.0, seed=120 + len(ranks) + ranks[0])
+    step = wl.make_step(cfg)                    # "distinct" over 24 sequences: all 12 adapters get pages
+    T = step.n_tokens
+    assert T >= 2816 and int((step.rank > 0).sum()) == 12
+    rng = np.random.default_rng(ranks[0])
+    step.token_adapter = rng.integers(-1, 12, size=T).astype(np.int32)
+    dev0 = resident_pool(step)
+    g = GpuStep(step, dev0, np.zeros((1, cfg.block_elems), dev0.dtype))
+    rtol, atol = TOL[cfg.dtype]
+    names = ["q", "k", "v"]
+    W = None
+    if with_base:
+        W = {n: wl.quantize((rng.standard_normal((cfg.hidden, step.proj[n].d_out)) / np.sqrt(cfg.hidden))
+                            .astype(np.float32), cfg.dtype) for n in names}
+    got = g.lora(names, w_base={n: to_dev(W[n]) for n in names} if W else None)
+    sel = np.arange(T, dtype=np.int32) if not with_base else np.unique(np.concatenate(
+        [rng.choice(T, size=300, replace=False), np.arange(0, 140), np.arange(T - 140, T)])).astype(np.int32)
+    none = step.token_adapter < 0
+    assert none.sum() > 100
+    ulp = 2.0 ** (-10 if cfg.dtype == "f16" else -7)
+    for n in names:
+        pr = step.proj[n]
+        want = oracle.lora_apply(dev0, cfg.dtype, step.acts["x"], step.token_adapter, step.rank, step.scale,
+                                 pr.a_tab_off, pr.a_row_base, pr.b_tab_off, pr.b_row_base, step.lora_tables,
+                                 pr.d_out, y_in=None if W else step.acts["base_" + n], w_base=W[n] if W else None,
+                                 sel=sel)
+        ok, worst, nbad = close(wl.dequantize(got[n][sel], cfg.dtype), want, rtol, atol)
+        assert ok, "%s: max err %g, %d elements out of tolerance" % (n, worst, nbad)
+        if not W:
+            base = wl.dequantize(step.acts["base_" + n], cfg.dtype)
+            assert np.array_equal(got[n][none], step.acts["base_" + n][none])     # rows without an adapter untouched
+            err = np.abs((wl.dequantize(got[n], cfg.dtype) - base) - (want - base))
+            assert err.max() <= ulp * (np.abs(want).max() + 1.0), (n, err.max())
+            assert np.abs(want - base)[~none].max() > 10 * atol
+        else:
+            # the branch is there: rows with an adapter differ from the dense product alone by more than the bound
+            dense = oracle.lora_apply(dev0, cfg.dtype, step.acts["x"], np.full(T, -1, np.int32), step.rank, step.scale,
+                                      pr.a_tab_off, pr.a_row_base, pr.b_tab_off, pr.b_row_base, step.lora_tables,
+                                      pr.d_out, w_base=W[n], sel=sel)
+            with_ad = ~none[sel]
+            assert np.abs(want - dense)[with_ad].max() > 10 * atol
+            # compare the branch itself at one spacing of the element type at the output's magnitude plus the
+            # rounding of the sum
+            err = np.abs((wl.dequantize(got[n][sel], cfg.dtype) - dense) - (want - dense))
+            assert err.max() <= 1.5 * ulp * (np.abs(want).max() + 1.0), (n, err.max())
+
+
+@pytest.mark.parametrize("dtype,bt,gqa", [("f16", 16, False), ("bf16", 16, True), ("f16", 32, False)])
+def test_attention_over_shared_prefix_blocks(dtype, bt, gqa):
+    """Sequences of one adapter share the physical blocks of a common prefix (paper section 4.1; KV of different
+    LoRAs is never shared, section 2.1): block ids repeat across tables.  Append writes only the sequences' own
+    blocks; attention reads the shared ones from every table that names them.  Prefill rows (matrix-core kernel)
+    and, in the grouped-query case, decode rows mixed in."""
+    kw = dict(n_q_heads=8, n_kv_heads=2, hidden=1024, decode_frac=0.4) if gqa else {}
+    cfg = small_cfg(dtype, block_tokens=bt, n_seqs=24, n_adapters=3, prefix_range=(40, 420), new_range=(1, 90),
+                    share_frac=0.85, n_dev_blocks=1500, swap_in_frac=0.0, seed=131 + bt + gqa, **kw)
+    step = wl.make_step(cfg)
+    ids, counts = np.unique(step.kv_tables[step.kv_tables >= 0], return_counts=True)
+    assert (counts > 1).sum() >= 20 and counts.max() >= 3, "the case shares too little"
+    dev0 = resident_pool(step)
+    g = GpuStep(step, dev0, np.zeros((1, cfg.block_elems), dev0.dtype))
+    n_kv, d, n_h = cfg.n_kv_heads, cfg.head_dim, cfg.n_q_heads
+    out = g.attention(append=True)
+    ref = dev0.copy()
+    oracle.kv_append(ref, cfg.dtype, bt, n_kv, d, step.cu_new, step.prefix_len, step.kv_tables, step.acts["k_new"],
+                     step.acts["v_new"])
+    assert np.array_equal(g.dev_image().view(np.uint8), ref.view(np.uint8)), "append touched a shared block"
+    shared = ids[counts > 1]
+    assert np.array_equal(ref[shared], dev0[shared])                      # shared blocks are prefix blocks: unchanged
+    want = oracle.paged_attention(ref, cfg.dtype, bt, n_kv, d, n_h, step.cu_new, step.prefix_len, step.kv_tables,
+                                  step.acts["q"])
+    ok, worst, nbad = close(wl.dequantize(out, cfg.dtype).reshape(want.shape), want, *TOL[cfg.dtype])
+    assert ok, "max err %g (%d bad)" % (worst, nbad)

@@ -302,3 +302,51 @@ def test_block_size_is_a_storage_detail():
     assert np.allclose(outs[0], _sdpa_reference(K.astype(np.float32).astype(np.float64),
                                                 V.astype(np.float32).astype(np.float64), q.astype(np.float64), P, n_h),
                        atol=1e-12)
+
+
+# ---------------------------------------------------------------- whole-sequence (numpy) form of O5
+def test_dense_form_equals_the_per_row_oracle_and_the_library():
+    """oracle/attention_dense.py evaluates the same definition for all rows of a sequence with library matrix
+    products; pinned against the per-row C oracle (paged, GQA, several sequences, bf16 storage, a block of 32
+    positions) and against library scaled-dot-product attention on the gathered K and V."""
+    from oracle.attention_dense import paged_attention_sequence
+    from helpers import resident_pool
+    for dtype, bt, seed in (("bf16", 16, 5), ("f16", 32, 6), ("f32", 16, 7)):
+        cfg = wl.LayerConfig("dense_pin", dtype, 256, 8, 2, 64, 300, 4, 3, (8,), ("q",), 5, (0, 150), (1, 40),
+                             block_tokens=bt, seed=seed)
+        step = wl.make_step(cfg, poison_fresh=False)
+        pool = resident_pool(step)
+        n_kv, d, n_h = cfg.n_kv_heads, cfg.head_dim, cfg.n_q_heads
+        oracle.kv_append(pool, dtype, bt, n_kv, d, step.cu_new, step.prefix_len, step.kv_tables,
+                         step.acts["k_new"], step.acts["v_new"])
+        rows = oracle.paged_attention(pool, dtype, bt, n_kv, d, n_h, step.cu_new, step.prefix_len, step.kv_tables,
+                                      step.acts["q"])
+        for i in range(cfg.n_seqs):
+            got = paged_attention_sequence(pool, dtype, bt, n_kv, d, n_h, step.cu_new, step.prefix_len,
+                                           step.kv_tables, step.acts["q"], i)
+            lo, hi = int(step.cu_new[i]), int(step.cu_new[i + 1])
+            np.testing.assert_allclose(got, rows[lo:hi], rtol=1e-11, atol=1e-13)
+            P = int(step.prefix_len[i])
+            K, V = oracle.kv_gather(pool, dtype, bt, n_kv, d, step.kv_tables[i], P + hi - lo)
+            qv = wl.dequantize(step.acts["q"], dtype).reshape(-1, n_h, d)[lo:hi]
+            np.testing.assert_allclose(got, _sdpa_reference(K, V, qv, P, n_h), rtol=1e-9, atol=1e-11)
+
+
+def test_dense_form_closed_forms():
+    """q = 0 gives the running mean of V over positions 0..P+j (pins the causal boundary and the prefix / fresh
+    seam of the dense form on its own); an explicit scale is honoured."""
+    from oracle.attention_dense import paged_attention_sequence
+    rng = np.random.default_rng(31)
+    L, n_kv, d, bt, P = 45, 2, 8, 16, 29
+    K, V = rng.standard_normal((L, n_kv, d)), rng.standard_normal((L, n_kv, d))
+    pool, table, Kq, Vq = _paged_from_contig(rng, K, V, bt)
+    N = L - P
+    q0 = np.zeros((N, 4 * d), np.float32)
+    got = paged_attention_sequence(pool, "f32", bt, n_kv, d, 4, [0, N], [P], table, q0, 0)
+    for j in range(N):
+        for h in range(4):
+            np.testing.assert_allclose(got[j, h], Vq[:P + j + 1, h // 2].mean(axis=0), rtol=1e-12, atol=1e-13)
+    q1 = rng.standard_normal((N, 4 * d)).astype(np.float32)
+    a = paged_attention_sequence(pool, "f32", bt, n_kv, d, 4, [0, N], [P], table, q1, 0, sm_scale=0.3)
+    b = oracle.paged_attention(pool, "f32", bt, n_kv, d, 4, [0, N], [P], table, q1, sm_scale=0.3)
+    np.testing.assert_allclose(a, b, rtol=1e-11, atol=1e-13)

@@ -204,3 +204,28 @@ def test_layer_lora_branch_enters_every_projection():
     n1 = lo.load(b["n1"], cfg.dtype)
     Wq = lo.load(W["v"], cfg.dtype)
     assert np.allclose(lo.load(b["v"], cfg.dtype), (n1 @ Wq.T).astype(np.float32), atol=1e-6)   # ... and scale 0 leaves the base
+
+
+def test_a_dropped_lora_branch_exceeds_the_layer_bounds():
+    """What the composed-layer bound of the GPU suite (8 spacings of the element type, relative plus absolute) can
+    see.  The mistake is planted in the oracle: the same layer computed with and without the LoRA branch on one
+    projection (the adapter shapes of the GPU cases: hidden 2048, MLP 3136, ranks 8-32, standard deviation 0.02).
+    A dropped branch on gate, up or down moves most output elements past fp16's bound (7.8e-3) and several per cent
+    of them past bf16's (6.3e-2); a dropped branch on q moves half of them past fp16's and a few per mille past
+    bf16's, which is why the suite holds the all-projection layer in fp16 as well."""
+    import copy
+    cfg = small_cfg("f16", hidden=2048, n_q_heads=16, n_kv_heads=16, head_dim=128, n_dev_blocks=700, n_adapters=5,
+                    ranks=(8, 16, 32), n_seqs=5, prefix_range=(0, 60), new_range=(20, 50), mlp_dim=3136, seed=51)
+    step = wl.make_step(cfg)
+    W = make_weights(cfg, np.random.default_rng(7))
+    h0, _ = lo.round_store(np.random.default_rng(8).normal(0, 1, (step.n_tokens, cfg.hidden)), cfg.dtype)
+    pos = positions_of(step)
+    full, _ = lo.layer_forward(cfg, step, pool_image(step), W, h0, pos)
+    a = lo.load(full, cfg.dtype)
+    for drop, min16, min_bf in (("gate", 0.5, 0.02), ("down", 0.5, 0.02), ("q", 0.25, 0.0005)):
+        dropped_step = copy.copy(step)
+        dropped_step.proj = {n: p for n, p in step.proj.items() if n != drop}
+        dropped, _ = lo.layer_forward(cfg, dropped_step, pool_image(step), W, h0, pos)
+        err = np.abs(a - lo.load(dropped, cfg.dtype))
+        assert (err > 8 * 2.0 ** -10 * (1 + np.abs(a))).mean() > min16, drop
+        assert (err > 8 * 2.0 ** -7 * (1 + np.abs(a))).mean() > min_bf, drop

@@ -64,3 +64,33 @@ def test_step_invariants(dist):
     # same seed, same step
     again = wl.make_step(cfg(adapter_dist=dist, n_seqs=50), with_acts=False, fill_content=False)
     assert np.array_equal(again.token_adapter, step.token_adapter) and np.array_equal(again.lora_tables, step.lora_tables)
+
+
+def test_shared_prefix_blocks_stay_within_one_adapter():
+    """share_frac > 0 (paper section 4.1: queries of one LoRA with a common beginning hang below the same nodes;
+    section 2.1: KV of different LoRAs is never shared): a physical block may sit in several tables, but only of
+    sequences with the same adapter, only as a leading full prefix block at the same index, and never the block
+    that a sequence's own new tokens are written to."""
+    cfg = wl.LayerConfig("share", "f16", 512, 4, 4, 128, 3000, 900, 3, (8,), ("q",), 60, (0, 400), (1, 40),
+                         share_frac=0.8, swap_in_frac=0.3, seed=5)
+    st = wl.make_step(cfg)
+    bt = cfg.block_tokens
+    owners = {}
+    for i in range(cfg.n_seqs):
+        nb = -(-(int(st.prefix_len[i]) + int(st.new_len[i])) // bt)
+        for k, b in enumerate(st.kv_tables[i, :nb]):
+            owners.setdefault(int(b), []).append((i, k))
+    shared = {b: o for b, o in owners.items() if len(o) > 1}
+    assert len(shared) > 20
+    for b, o in shared.items():
+        assert len({int(st.seq_adapter[i]) for i, _ in o}) == 1          # one adapter
+        assert len({k for _, k in o}) == 1                                # the same place in every table
+        for i, k in o:
+            assert (k + 1) * bt <= int(st.prefix_len[i])                  # a full prefix block, not the append target
+    assert len(np.unique(st.content_ids)) == len(st.content_ids)          # every block has one content row
+    assert not np.isin(st.fresh_block_ids, list(shared)).any()
+    # the knob off: the same seed shares nothing
+    st0 = wl.make_step(cfg.scaled(share_frac=0.0))
+    ids, counts = np.unique(st0.kv_tables[st0.kv_tables >= 0], return_counts=True)
+    assert counts.max() == 1
+    assert np.array_equal(st0.prefix_len, st.prefix_len) and np.array_equal(st0.seq_adapter, st.seq_adapter)
