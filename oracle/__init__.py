@@ -14,8 +14,26 @@ import numpy as np
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "liborc.so")
 _lib = None
+_default_threads = None
 
 DTYPE_CODE = {"f32": 0, "f16": 1, "bf16": 2}
+
+
+def set_variant(name):
+    """Which build of flp_oracle.c the calls below go to: "parity" (double running sums; the default and the only
+    one any comparison may use) or "f32acc" (fp32 running sums, -O3: the benchmark's second CPU timing)."""
+    global _lib, _LIB_PATH
+    _LIB_PATH = os.path.join(_HERE, {"parity": "liborc.so", "f32acc": "liborc_f32acc.so"}[name])
+    _lib = None
+
+
+def set_threads(n):
+    """Number of OpenMP threads of the following oracle calls (0: all cores again)."""
+    global _default_threads
+    omp = C.CDLL("libgomp.so.1")
+    if _default_threads is None:
+        _default_threads = int(omp.omp_get_max_threads())      # what the environment gave the process
+    omp.omp_set_num_threads(int(n) if n > 0 else _default_threads)
 
 
 def lib():

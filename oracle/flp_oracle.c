@@ -37,6 +37,14 @@
 #include <stdlib.h>
 #include <string.h>
 
+/* Type of the running sums of the LoRA and attention products.  double in the parity build (the only one the
+ * tests use); the benchmark's cpu_baseline leg also times a second build with -DORC_ACC_T=float (fp32
+ * accumulation, what a production CPU kernel would do), which no parity check ever loads. */
+#ifndef ORC_ACC_T
+#define ORC_ACC_T double
+#endif
+typedef ORC_ACC_T acc_t;
+
 /* ------------------------------------------------------------------ formats */
 static double half_to_double(uint16_t h) {
   int sign = (h >> 15) & 1;
@@ -221,7 +229,7 @@ int orc_lora_apply(const void* pool, int dtype, int64_t block_elems,
     double* y = out + (int64_t)i * d_out;
     for (int32_t o = 0; o < d_out; ++o) {
       if (w_base) {
-        double acc = 0.0;
+        acc_t acc = 0.0;
         for (int32_t c = 0; c < d_in; ++c)
           acc += load_elem(x, dtype, t * ld_x + c) * load_elem(w_base, dtype, (int64_t)c * d_out + o);
         y[o] = acc;
@@ -236,14 +244,14 @@ int orc_lora_apply(const void* pool, int dtype, int64_t block_elems,
     const int32_t* ta = block_tables + a_tab_off[a];
     const int32_t* tb = block_tables + b_tab_off[a];
     for (int32_t rho = 0; rho < r; ++rho) {
-      double acc = 0.0;
+      acc_t acc = 0.0;
       for (int32_t c = 0; c < d_in; ++c)
         acc += load_elem(x, dtype, t * ld_x + c) *
                load_elem(pool, dtype, lora_elem(ta, block_elems, d_in, (int64_t)a_row_base[a] + rho, c));
       v[rho] = acc;
     }
     for (int32_t o = 0; o < d_out; ++o) {
-      double acc = 0.0;
+      acc_t acc = 0.0;
       for (int32_t rho = 0; rho < r; ++rho)
         acc += v[rho] * load_elem(pool, dtype, lora_elem(tb, block_elems, d_out, (int64_t)b_row_base[a] + rho, o));
       y[o] += (double)scale[a] * acc;
@@ -371,7 +379,7 @@ int orc_paged_attention(const void* pool, int dtype, int32_t bt, int32_t n_kv, i
       double m = -INFINITY;
       for (int32_t k = 0; k <= p; ++k) {
         int64_t base = (int64_t)table[k / bt] * block_elems;
-        double acc = 0.0;
+        acc_t acc = 0.0;
         for (int32_t c = 0; c < d; ++c)
           acc += load_elem(q, dtype, ((int64_t)t * n_h + h) * d + c) *
                  load_elem(pool, dtype, base + k_off(bt, d, g, k % bt, c));
@@ -391,7 +399,7 @@ int orc_paged_attention(const void* pool, int dtype, int32_t bt, int32_t n_kv, i
       if (wsum) wsum[(int64_t)idx * n_h + h] = tot;
       double* o = out + ((int64_t)idx * n_h + h) * d;
       for (int32_t c = 0; c < d; ++c) {
-        double acc = 0.0;
+        acc_t acc = 0.0;
         for (int32_t k = 0; k <= p; ++k) {
           int64_t base = (int64_t)table[k / bt] * block_elems;
           acc += w[k] * load_elem(pool, dtype, base + v_off(bt, n_kv, d, g, k % bt, c));
