@@ -19,6 +19,8 @@ flp_status flp_launch_copy_blocks(const uint8_t*, uint8_t*, const int32_t*, cons
   std::abort();
 }
 flp_status flp_launch_stage_copy(const void*, void*, size_t, hipStream_t) { std::abort(); }
+// the fixed scratch array belongs to the GPU build; pool creation tolerates that its set-up fails
+flp_status flp_static_scratch_setup(int, void**) { return FLP_EHIP; }
 
 #define REQUIRE(cond)                                                                       \
   do {                                                                                      \
