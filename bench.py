@@ -211,11 +211,17 @@ class Bench:
         self.max_rank = int(max(cfg.ranks))
         # default priority, all three.  The two directions of the host link are independent: write-backs and
         # fetches get a stream each.
-        self.s_comp, self.s_in, self.s_out = torch.cuda.Stream(), torch.cuda.Stream(), torch.cuda.Stream()
+        self.s_comp = torch.cuda.Stream()
+        self.planner = None
         if args.one_stream:
             self.s_in = self.s_out = self.s_comp
         elif args.one_swap_stream:
-            self.s_out = self.s_in
+            self.s_in = self.s_out = torch.cuda.Stream()
+        else:
+            # the library's planner (include/flsched.h) owns the two move streams and their ordering
+            from paper_2505_03756_amd import flsched
+            self.planner = flsched.Planner(self.pool)
+            self.s_in = self.s_out = None
         torch.cuda.synchronize()
         log("%s: pool %d x %d KiB (%.1f GiB), host tier %d blocks, %d slots, set-up %.1f s" % (
             cfg.name, nd, cfg.block_bytes >> 10, nd * cfg.block_bytes / 2 ** 30, nh, S, time.time() - t0))
@@ -319,17 +325,24 @@ class Bench:
             if st.n_tokens > self.t_cap:
                 raise SystemExit("bench.py: a step of %d tokens exceeds the activation buffers (%d)" % (st.n_tokens, self.t_cap))
             self.upload(st, g)
-            if not one:
-                if self.prev_comp is not None:
-                    self.s_out.wait_event(self.prev_comp)
-                if self.prev_out is not None and self.s_in is not self.s_out:
-                    self.s_in.wait_event(self.prev_out)
-            self.swap(st, self.s_in, self.s_out)
-            ev_out, ev_in = torch.cuda.Event(), torch.cuda.Event()
-            ev_out.record(self.s_out)
-            ev_in.record(self.s_in)
-            if self.prev_in is not None and not one:
-                self.s_comp.wait_event(self.prev_in)
+            if self.planner is not None:
+                # request g = the queries that join at step g + 1, with their fetches and the write-backs of what left
+                self.planner.submit(g, st.swap_in_host, st.swap_in_dev, st.swap_out_dev, st.swap_out_host)
+                if g >= 1:
+                    self.planner.stream_wait(g - 1, self.s_comp)     # this step's joiners were fetched by request g - 1
+            else:
+                if not one:
+                    if self.prev_comp is not None:
+                        self.s_out.wait_event(self.prev_comp)
+                    if self.prev_out is not None and self.s_in is not self.s_out:
+                        self.s_in.wait_event(self.prev_out)
+                self.swap(st, self.s_in, self.s_out)
+                ev_out, ev_in = torch.cuda.Event(), torch.cuda.Event()
+                ev_out.record(self.s_out)
+                ev_in.record(self.s_in)
+                if self.prev_in is not None and not one:
+                    self.s_comp.wait_event(self.prev_in)
+                self.prev_in, self.prev_out = ev_in, ev_out
             ev = None
             self.lora_qkv(st, self.s_comp)
             self.kv_append(st, self.s_comp)
@@ -343,7 +356,9 @@ class Bench:
             done = torch.cuda.Event()
             done.record(self.s_comp)
             self.comp_done[g % 3] = done
-            self.prev_comp, self.prev_in, self.prev_out = done, ev_in, ev_out
+            self.prev_comp = done
+            if self.planner is not None:
+                self.planner.compute_enqueued(self.s_comp)
             self.step_no += 1
             recs.append(dict(st=st, ev=ev))
         return recs
@@ -356,6 +371,8 @@ class Bench:
         import gc
         torch = self.torch
         torch.cuda.synchronize()
+        if self.planner is not None:
+            self.planner.close()
         self.pool.close()
         for k in list(self.__dict__):
             if k not in ("cfg", "tc", "args", "over"):
@@ -504,7 +521,8 @@ def run_workload(name, args, headline):
                    "swap": ("one stream, no overlap" if args.one_stream else
                             ("write-backs and fetches of step k on %s beside the compute of step k; the compute of "
                              "step k + 1 waits for the fetches" % ("one stream of their own" if args.one_swap_stream
-                                                                   else "a stream each")))
+                                                                   else "a stream each, issued and ordered by the "
+                                                                        "library's planner (flsched.h)")))
                    if tc.mode != "static" else "none in this workload"},
         "roofline": roof,
         "swap_traffic": {"GB_per_step_mean": round(float(np.mean(swap_GB)), 4), "GB_per_step_max": round(max(swap_GB), 4),

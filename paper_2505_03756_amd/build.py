@@ -10,7 +10,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libflpool.so")
-SOURCES = ["pool.cpp", "dispatch.cpp", "cache_manager.cpp", "swap.hip", "attention.hip", "attention_mfma.hip", "lora.hip", "lora_mfma.hip", "gemm.hip", "layer.hip", "static_scratch.hip"]
+SOURCES = ["pool.cpp", "dispatch.cpp", "cache_manager.cpp", "sched.cpp", "swap.hip", "attention.hip", "attention_mfma.hip", "lora.hip", "lora_mfma.hip", "gemm.hip", "layer.hip", "static_scratch.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-I" + os.path.join(ROOT, "include"), "-I" + CSRC,
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wall", "-Wno-unused-function",

@@ -73,6 +73,9 @@ flp_status flp_stage_acquire(flp_pool* pool, size_t bytes, FlpStageSlot** slot);
 flp_status flp_stage_upload(FlpStageSlot* slot, size_t bytes, hipStream_t stream);
 flp_status flp_stage_release(FlpStageSlot* slot, hipStream_t stream);
 flp_status flp_workspace(flp_pool* pool, size_t bytes, void** out);
+// the host-side checks of flp_pool_swap_in (src_tier 1) / flp_pool_swap_out (src_tier 0) without enqueuing anything
+flp_status flp_swap_check(flp_pool* pool, int32_t n, const int32_t* src_ids, const int32_t* dst_ids, int src_tier,
+                          const char* who);
 
 // A workspace of fixed size that the caller of the LoRA path brings along instead of the pool's growing one:
 // `resolve` returns its device address for the pool's device (called only after the size check has passed).

@@ -260,14 +260,9 @@ flp_status flp_workspace(flp_pool* p, size_t bytes, void** out) {
 // (Paper sections 3.2 / 5.3: the swapper's ordered decisions are carried out as block
 // moves, swap-out before swap-in when the device tier is full; section 4.3: on a stream,
 // asynchronously to the compute of the requests that are ready.)
-static flp_status swap_common(flp_pool* p, int32_t n, const int32_t* src_ids, const int32_t* dst_ids,
-                              int src_tier, void* hip_stream, const char* who) {
-  if (!p || n < 0 || (n > 0 && (!src_ids || !dst_ids))) {
-    flp_set_error("%s: invalid argument", who);
-    return FLP_EINVAL;
-  }
-  if (n == 0) return FLP_OK;
-  std::lock_guard<std::mutex> lk(p->mu);
+// argument and list checks of a swap call (with the pool's lock held)
+static flp_status swap_check_locked(flp_pool* p, int32_t n, const int32_t* src_ids, const int32_t* dst_ids, int src_tier,
+                                    const char* who) {
   const int dst_tier = 1 - src_tier;
   FlpFreeList& fs = p->tier[src_tier];
   FlpFreeList& fd = p->tier[dst_tier];
@@ -283,6 +278,29 @@ static flp_status swap_common(flp_pool* p, int32_t n, const int32_t* src_ids, co
     }
     fd.stamp[(size_t)dst_ids[k]] = gen;
   }
+  return FLP_OK;
+}
+
+flp_status flp_swap_check(flp_pool* p, int32_t n, const int32_t* src_ids, const int32_t* dst_ids, int src_tier,
+                          const char* who) {
+  if (!p || n < 0 || (n > 0 && (!src_ids || !dst_ids))) {
+    flp_set_error("%s: invalid argument", who);
+    return FLP_EINVAL;
+  }
+  std::lock_guard<std::mutex> lk(p->mu);
+  return swap_check_locked(p, n, src_ids, dst_ids, src_tier, who);
+}
+
+static flp_status swap_common(flp_pool* p, int32_t n, const int32_t* src_ids, const int32_t* dst_ids,
+                              int src_tier, void* hip_stream, const char* who) {
+  if (!p || n < 0 || (n > 0 && (!src_ids || !dst_ids))) {
+    flp_set_error("%s: invalid argument", who);
+    return FLP_EINVAL;
+  }
+  if (n == 0) return FLP_OK;
+  std::lock_guard<std::mutex> lk(p->mu);
+  const int dst_tier = 1 - src_tier;
+  FLP_TRY(swap_check_locked(p, n, src_ids, dst_ids, src_tier, who));
   hipStream_t stream = (hipStream_t)hip_stream;
   FlpStageSlot* slot = nullptr;
   size_t bytes = sizeof(int32_t) * 2 * (size_t)n;
