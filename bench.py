@@ -64,6 +64,9 @@ def parse():
     ap.add_argument("--dev-blocks", type=int, default=None, help="override the pool's device block count")
     ap.add_argument("--host-blocks", type=int, default=None)
     ap.add_argument("--seqs", type=int, default=None, help="override the number of sequence slots")
+    ap.add_argument("--prefix-range", type=int, nargs=2, default=None, metavar=("LO", "HI"),
+                    help="override the range the prefix lengths are drawn from (few long sequences: --seqs 4 "
+                         "--prefix-range 16383 16383)")
     ap.add_argument("--one-stream", action="store_true", help="moves and compute on ONE stream (no overlap): the "
                     "baseline the asynchronous pipeline is compared with")
     ap.add_argument("--one-swap-stream", action="store_true", help="write-backs and fetches share one stream beside "
@@ -145,6 +148,8 @@ class Bench:
                         n_host_blocks=int(cfg.n_host_blocks / f))
         if args.seqs is not None:
             over["n_seqs"] = int(args.seqs)
+        if args.prefix_range is not None:
+            over["prefix_range"] = (int(args.prefix_range[0]), int(args.prefix_range[1]))
         if over:
             cfg = cfg.scaled(**over)
         self.over = over

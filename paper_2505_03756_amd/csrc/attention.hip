@@ -182,7 +182,9 @@ __global__ __launch_bounds__(256) void attn_rows_kernel(FlpAttnArgs a, const Flp
     for (int c = 0; c < C::CPL; ++c) acc[c] = 0.f;
 
     const int nblk = (ctx + BT - 1) / BT;
-    for (int b = 0; b < nblk; ++b) {
+    const bool split = u.n_split > 1;                   // this unit covers only the groups [g_lo, g_hi) of the context
+    const int b_lo = split ? u.g_lo : 0, b_hi = split ? (u.g_hi < nblk ? u.g_hi : nblk) : nblk;
+    for (int b = b_lo; b < b_hi; ++b) {
       // group b of 16 positions: group b % hpb of block b / hpb
       const ST* __restrict__ base = pool + (int64_t)table[b / hpb] * a.block_elems + BT * (b % hpb) * D;
       const ST* __restrict__ vbase = pool + (int64_t)table[b / hpb] * a.block_elems + v_region + BT * (b % hpb);
@@ -242,11 +244,52 @@ __global__ __launch_bounds__(256) void attn_rows_kernel(FlpAttnArgs a, const Flp
         acc[c] = acc[c] * alpha + part;
       }
     }
+    if (split) {
+      // unnormalised piece: running maximum (in the exponent's units), sum of weights, channels
+      float* pp = a.partials + (((int64_t)u.part_row * a.n_h + h) * a.max_split + u.split) * (D + 2);
+      if (lane == 0) {
+        pp[0] = m;
+        pp[1] = l;
+      }
+#pragma unroll
+      for (int c = 0; c < C::CPL; ++c) pp[2 + lane + 64 * c] = acc[c];
+      continue;
+    }
     const float inv = 1.f / l;
     ST* op = reinterpret_cast<ST*>(a.out) + ((int64_t)t * a.n_h + h) * D;
 #pragma unroll
     for (int c = 0; c < C::CPL; ++c) op[lane + 64 * c] = S::from_float(acc[c] * inv);
   }
+}
+
+// Merge of the split-KV pieces of one (token, head) row: out = sum_i acc_i 2^(m_i - M) / sum_i l_i 2^(m_i - M)
+// with M = max_i m_i, the pieces taken in piece order.  One wave per row, four heads per workgroup.
+template <typename S, int D>
+__global__ __launch_bounds__(256) void attn_merge_kernel(FlpAttnArgs a, const int32_t* __restrict__ merge_tok,
+                                                         const int32_t* __restrict__ merge_nsplit) {
+  typedef typename S::storage ST;
+  constexpr int CPL = D / 64;
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int row = blockIdx.x, h = blockIdx.y * 4 + wave;
+  if (h >= a.n_h) return;
+  const int t = merge_tok[row], ns = merge_nsplit[row];
+  const float* pp = a.partials + ((int64_t)row * a.n_h + h) * a.max_split * (D + 2);
+  float M = -INFINITY;
+  for (int i = 0; i < ns; ++i) M = fmaxf(M, pp[(int64_t)i * (D + 2)]);
+  float l = 0.f, acc[CPL];
+#pragma unroll
+  for (int c = 0; c < CPL; ++c) acc[c] = 0.f;
+  for (int i = 0; i < ns; ++i) {
+    const float* q = pp + (int64_t)i * (D + 2);
+    const float w = exp2f(q[0] - M);                    // a piece without visible keys has m = -inf, l = 0: weight 0
+    l = fmaf(q[1], w, l);
+#pragma unroll
+    for (int c = 0; c < CPL; ++c) acc[c] = fmaf(q[2 + lane + 64 * c], w, acc[c]);
+  }
+  const float inv = 1.f / l;
+  ST* op = reinterpret_cast<ST*>(a.out) + ((int64_t)t * a.n_h + h) * D;
+#pragma unroll
+  for (int c = 0; c < CPL; ++c) op[lane + 64 * c] = S::from_float(acc[c] * inv);
 }
 
 }  // namespace
@@ -298,6 +341,15 @@ flp_status flp_launch_attn_rows(int dtype, int head_dim, const FlpAttnArgs& a, c
   if (n_units <= 0) return FLP_OK;
   dim3 grid((unsigned)n_units, (unsigned)((a.n_h + 3) / 4));
   FLP_DISPATCH(attn_rows_kernel, dtype, head_dim, grid, dim3(256), stream, a, units_dev);
+  FLP_TRY_HIP(hipGetLastError());
+  return FLP_OK;
+}
+
+flp_status flp_launch_attn_merge(int dtype, int head_dim, const FlpAttnArgs& a, const int32_t* merge_tok_dev,
+                                 const int32_t* merge_nsplit_dev, int32_t n_rows, hipStream_t stream) {
+  if (n_rows <= 0) return FLP_OK;
+  dim3 grid((unsigned)n_rows, (unsigned)((a.n_h + 3) / 4));
+  FLP_DISPATCH(attn_merge_kernel, dtype, head_dim, grid, dim3(256), stream, a, merge_tok_dev, merge_nsplit_dev);
   FLP_TRY_HIP(hipGetLastError());
   return FLP_OK;
 }

@@ -168,16 +168,28 @@ extern "C" flp_status flp_paged_prefix_attention(flp_pool* p, const flp_attn_bat
   std::vector<FlpAttnUnit> units;
   std::vector<int64_t> cost;
   constexpr int kTokPerUnit = 4;
+  // A launch of a handful of matrix-core items (a few decode sequences under grouped-query attention) would leave
+  // most of the chip idle: such sequences go to the row-streaming kernel instead, where their long contexts are
+  // split over many waves (below).
+  int64_t mfma_items_est = 0;
+  if (mfma_ok)
+    for (int32_t i = 0; i < b->n_seqs; ++i) {
+      const int64_t n = b->cu_new[i + 1] - b->cu_new[i];
+      if (G * n >= 8) mfma_items_est += (int64_t)n_kv * ((G * n + kMfmaRowsPerItem - 1) / kMfmaRowsPerItem);
+    }
+  const bool small_launch = mfma_items_est < 128;
   // matrix-core items: the row tiles of one (sequence, kv head) are dealt to ONE of 8 queues and
   // the queues are interleaved, so that under round-robin dispatch of workgroups over the 8
   // XCDs the tiles that re-read the same K/V run on the same XCD and share its L2.
   std::vector<FlpMfmaItem> queue[8];
   int next_q = 0;
+  std::vector<int32_t> row_seqs;                      // sequences of the row-streaming kernel, heaviest first
+  int64_t row_tokens = 0;
   for (int32_t i : seq_order) {
     const int32_t n = b->cu_new[i + 1] - b->cu_new[i];
     if (n <= 0) continue;
     const int64_t blocks_i = ((int64_t)b->prefix_len[i] + n + p->cfg.block_tokens - 1) / p->cfg.block_tokens;
-    if (mfma_ok && (int64_t)G * n >= 8 && blocks_i <= kMfmaMaxBlocks) {
+    if (mfma_ok && (int64_t)G * n >= 8 && blocks_i <= kMfmaMaxBlocks && !(small_launch && n <= kTokPerUnit)) {
       const int32_t R = G * n;
       for (int g = 0; g < n_kv; ++g) {
         for (int32_t r0 = 0; r0 < R; r0 += kMfmaRowsPerItem)
@@ -185,8 +197,45 @@ extern "C" flp_status flp_paged_prefix_attention(flp_pool* p, const flp_attn_bat
         next_q = (next_q + 1) & 7;
       }
     } else {
+      row_seqs.push_back(i);
+      row_tokens += n;
+    }
+  }
+  // Split-KV.  The row kernel runs one wave per (token, head); with few rows and long contexts (a handful of decode
+  // sequences at 16 k tokens) that is far fewer waves than the chip holds.  Below kSplitBelow waves every token
+  // becomes a unit of its own and its context is cut into pieces of at least kMinGroups groups of 16 positions, each
+  // piece a wave; a second kernel merges the pieces of a row in piece order.
+  constexpr int64_t kSplitBelow = 2048, kSplitTarget = 8192;
+  constexpr int kMinGroups = 16, kMaxSplit = 64;
+  const int64_t row_waves = row_tokens * b->n_q_heads;
+  const int want_split = row_waves > 0 && row_waves < kSplitBelow
+                             ? (int)std::min<int64_t>(kMaxSplit, (kSplitTarget + row_waves - 1) / row_waves) : 1;
+  std::vector<int32_t> merge_tok, merge_nsplit;
+  int max_split = 1;
+  for (int32_t i : row_seqs) {
+    const int32_t n = b->cu_new[i + 1] - b->cu_new[i];
+    if (want_split > 1) {
+      for (int32_t j = 0; j < n; ++j) {
+        const int32_t groups = (b->prefix_len[i] + j + 1 + 15) / 16;
+        const int ns = std::max(1, std::min(want_split, groups / kMinGroups));
+        if (ns == 1) {
+          units.push_back(FlpAttnUnit{i, j, 1, 1, 0, 0, 0, 0});
+          cost.push_back(groups);
+          continue;
+        }
+        const int32_t row = (int32_t)merge_tok.size();
+        merge_tok.push_back(b->cu_new[i] + j);
+        merge_nsplit.push_back(ns);
+        max_split = std::max(max_split, ns);
+        for (int sidx = 0; sidx < ns; ++sidx) {
+          const int32_t lo = (int32_t)((int64_t)groups * sidx / ns), hi = (int32_t)((int64_t)groups * (sidx + 1) / ns);
+          units.push_back(FlpAttnUnit{i, j, 1, ns, sidx, lo, hi, row});
+          cost.push_back(hi - lo);
+        }
+      }
+    } else {
       for (int32_t j0 = 0; j0 < n; j0 += kTokPerUnit) {
-        FlpAttnUnit u{i, j0, std::min(kTokPerUnit, n - j0), 0};
+        FlpAttnUnit u{i, j0, std::min(kTokPerUnit, n - j0), 1, 0, 0, 0, 0};
         units.push_back(u);
         cost.push_back((int64_t)u.n_tok * (b->prefix_len[i] + j0 + u.n_tok));
       }
@@ -200,22 +249,38 @@ extern "C" flp_status flp_paged_prefix_attention(flp_pool* p, const flp_attn_bat
   const size_t n_items = qmax * 8;
   if (units.empty() && n_items == 0) return FLP_OK;
 
-  std::vector<uint8_t> blob(units.size() * sizeof(FlpAttnUnit) + n_items * sizeof(FlpMfmaItem));
+  const size_t units_bytes = units.size() * sizeof(FlpAttnUnit), items_bytes = n_items * sizeof(FlpMfmaItem);
+  const size_t n_merge = merge_tok.size();
+  std::vector<uint8_t> blob(units_bytes + items_bytes + 2 * n_merge * sizeof(int32_t));
   FlpAttnUnit* hu = (FlpAttnUnit*)blob.data();
   for (size_t k = 0; k < order.size(); ++k) hu[k] = units[order[k]];
-  FlpMfmaItem* hi = (FlpMfmaItem*)(blob.data() + units.size() * sizeof(FlpAttnUnit));
+  FlpMfmaItem* hi = (FlpMfmaItem*)(blob.data() + units_bytes);
   for (size_t s = 0; s < qmax; ++s)
     for (int x = 0; x < 8; ++x) hi[8 * s + x] = s < queue[x].size() ? queue[x][s] : FlpMfmaItem{0, 0, 0, 0};
+  if (n_merge) {
+    int32_t* hm = (int32_t*)(blob.data() + units_bytes + items_bytes);
+    memcpy(hm, merge_tok.data(), n_merge * sizeof(int32_t));
+    memcpy(hm + n_merge, merge_nsplit.data(), n_merge * sizeof(int32_t));
+  }
+  void* partials = nullptr;
+  if (n_merge)
+    FLP_TRY(flp_attn_workspace(p, n_merge * (size_t)b->n_q_heads * max_split * (p->cfg.head_dim + 2) * sizeof(float),
+                               &partials));
 
   StagedSeqs st;
   FLP_TRY(stage_seqs(p, b, blob.data(), blob.size(), stream, &st));
   FlpAttnArgs a = make_args(p, b, st);
+  a.partials = (float*)partials;
+  a.max_split = max_split;
   const FlpAttnUnit* du = (const FlpAttnUnit*)st.units;
-  const FlpMfmaItem* di = (const FlpMfmaItem*)((const uint8_t*)st.units + units.size() * sizeof(FlpAttnUnit));
+  const FlpMfmaItem* di = (const FlpMfmaItem*)((const uint8_t*)st.units + units_bytes);
+  const int32_t* dm = (const int32_t*)((const uint8_t*)st.units + units_bytes + items_bytes);
   flp_status s0 = flp_launch_attn_mfma(p->cfg.dtype, a, di, (int32_t)n_items, stream);
   flp_status s1 = flp_launch_attn_rows(p->cfg.dtype, p->cfg.head_dim, a, du, (int32_t)units.size(), stream);
+  flp_status s3 = s1 == FLP_OK ? flp_launch_attn_merge(p->cfg.dtype, p->cfg.head_dim, a, dm, dm + n_merge,
+                                                        (int32_t)n_merge, stream) : FLP_OK;
   flp_status s2 = flp_stage_release(st.slot, stream);
-  return s0 != FLP_OK ? s0 : (s1 != FLP_OK ? s1 : s2);
+  return s0 != FLP_OK ? s0 : (s1 != FLP_OK ? s1 : (s3 != FLP_OK ? s3 : s2));
 }
 
 // ------------------------------------------------------------------------------- LoRA

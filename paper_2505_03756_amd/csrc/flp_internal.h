@@ -63,6 +63,8 @@ struct flp_pool {
   int stage_next = 0;
   void* work = nullptr;           // device workspace (LoRA intermediates), grown on demand
   size_t work_cap = 0;
+  void* attn_work = nullptr;      // device workspace of the attention call (split-KV partial results)
+  size_t attn_work_cap = 0;
   mutable std::mutex mu;          // guards the free lists, the staging slots and the workspace
 };
 
@@ -103,7 +105,10 @@ struct FlpAppendUnit {   // the slots [s0, s1) of the 16-position group `blk_idx
   int32_t seq, blk_idx, s0, s1, t_first, pad0, pad1, pad2;
 };
 struct FlpAttnUnit {     // new tokens [j0, j0+n_tok) of sequence `seq`
-  int32_t seq, j0, n_tok, pad;
+  int32_t seq, j0, n_tok;
+  // split-KV (few long sequences): with n_split > 1 the unit is ONE token and covers only the 16-position groups
+  // [g_lo, g_hi) of its context; its unnormalised result goes to row part_row of the partials buffer, piece `split`
+  int32_t n_split, split, g_lo, g_hi, part_row;
 };
 
 struct FlpMfmaItem {     // query rows [r0, r0+n_rows) of (sequence, kv head g); n_rows == 0: padding
@@ -124,12 +129,19 @@ struct FlpAttnArgs {
   const int32_t* cu_new;       // device copies
   const int32_t* prefix_len;
   float scale_log2e;
+  float* partials;             // split-KV: [part_row][n_h][max_split][head_dim + 2] fp32 (running max, sum, channels)
+  int32_t max_split;
 };
 
 flp_status flp_launch_kv_append(int dtype, int head_dim, const FlpAttnArgs& a, const FlpAppendUnit* units_dev,
                                 int32_t n_units, hipStream_t stream);
 flp_status flp_launch_attn_rows(int dtype, int head_dim, const FlpAttnArgs& a, const FlpAttnUnit* units_dev,
                                 int32_t n_units, hipStream_t stream);
+// split-KV: one merged row per (partials row, head): token t = merge_tok[row], n_split[row] pieces combined in
+// piece order (so the result does not depend on which piece finished first)
+flp_status flp_launch_attn_merge(int dtype, int head_dim, const FlpAttnArgs& a, const int32_t* merge_tok_dev,
+                                 const int32_t* merge_nsplit_dev, int32_t n_rows, hipStream_t stream);
+flp_status flp_attn_workspace(flp_pool* pool, size_t bytes, void** out);
 
 flp_status flp_launch_attn_mfma(int dtype, const FlpAttnArgs& a, const FlpMfmaItem* items_dev, int32_t n_items,
                                 hipStream_t stream);

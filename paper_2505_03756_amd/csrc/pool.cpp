@@ -134,6 +134,7 @@ extern "C" flp_status flp_pool_destroy(flp_pool* p) {
     if (s.dev) (void)hipFree(s.dev);
   }
   if (p->work) (void)hipFree(p->work);
+  if (p->attn_work) (void)hipFree(p->attn_work);
   if (p->own_dev && p->dev_base) (void)hipFree(p->dev_base);
   if (p->own_host && p->host_base) (void)hipHostFree(p->host_base);
   delete p;
@@ -253,6 +254,20 @@ flp_status flp_workspace(flp_pool* p, size_t bytes, void** out) {
     p->work_cap = cap;
   }
   *out = p->work;
+  return FLP_OK;
+}
+
+flp_status flp_attn_workspace(flp_pool* p, size_t bytes, void** out) {
+  if (p->attn_work_cap < bytes) {
+    FLP_TRY_HIP(hipDeviceSynchronize());                 // earlier launches may still be reading the old buffer
+    if (p->attn_work) FLP_TRY_HIP(hipFree(p->attn_work));
+    p->attn_work = nullptr;
+    p->attn_work_cap = 0;
+    size_t cap = (bytes + (1 << 20)) & ~(size_t)((1 << 20) - 1);
+    FLP_TRY_HIP(hipMalloc(&p->attn_work, cap));
+    p->attn_work_cap = cap;
+  }
+  *out = p->attn_work;
   return FLP_OK;
 }
 

@@ -500,3 +500,33 @@ def test_attention_over_shared_prefix_blocks(dtype, bt, gqa):
                                   step.acts["q"])
     ok, worst, nbad = close(wl.dequantize(out, cfg.dtype).reshape(want.shape), want, *TOL[cfg.dtype])
     assert ok, "max err %g (%d bad)" % (worst, nbad)
+
+
+@pytest.mark.parametrize("dtype,heads,kv,d,seqs,prefix,new", [
+    ("bf16", 32, 32, 128, 3, (3000, 9000), (1, 1)),       # a handful of decode sequences with long contexts
+    ("f16", 8, 8, 64, 2, (2000, 5000), (1, 1)),
+    ("f32", 4, 4, 128, 2, (1500, 2500), (1, 1)),
+    ("bf16", 16, 2, 128, 4, (4000, 12000), (1, 1)),       # grouped-query decode: too few matrix-core items, rows + split
+    ("f16", 8, 8, 128, 5, (100, 6000), (1, 3)),           # short and long contexts mixed, up to three new tokens
+])
+def test_split_kv_for_few_long_sequences(dtype, heads, kv, d, seqs, prefix, new):
+    """Few rows over long contexts: the context of a row is cut into pieces, a wave each, and the pieces are merged in
+    a fixed order (the split-KV form of the same softmax).  Against the oracle, and twice for identical bits."""
+    cfg = small_cfg(dtype, hidden=heads * d, n_q_heads=heads, n_kv_heads=kv, head_dim=d, n_seqs=seqs,
+                    prefix_range=prefix, new_range=new, decode_frac=1.0 if new == (1, 1) else 0.0, n_adapters=2,
+                    ranks=(8,), projections=("q",), n_dev_blocks=seqs * (prefix[1] // 16 + 3) + 64, swap_in_frac=0.0,
+                    seed=500 + heads + seqs)
+    step = wl.make_step(cfg)
+    assert step.n_tokens * heads < 2048                        # under the kernel's fill: the split path is taken
+    dev0 = resident_pool(step)
+    g = GpuStep(step, dev0, np.zeros((1, cfg.block_elems), dev0.dtype))
+    out1 = g.attention(append=True)
+    out2 = g.attention(append=False)                           # the fresh K/V are in place: same inputs, same bits
+    assert np.array_equal(out1, out2)
+    ref = dev0.copy()
+    oracle.kv_append(ref, dtype, 16, kv, d, step.cu_new, step.prefix_len, step.kv_tables, step.acts["k_new"],
+                     step.acts["v_new"])
+    want = oracle.paged_attention(ref, dtype, 16, kv, d, heads, step.cu_new, step.prefix_len, step.kv_tables,
+                                  step.acts["q"])
+    ok, worst, nbad = close(wl.dequantize(out1, dtype).reshape(want.shape), want, *TOL[dtype])
+    assert ok, "max err %g (%d bad)" % (worst, nbad)
