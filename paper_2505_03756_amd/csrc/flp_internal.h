@@ -65,6 +65,7 @@ struct flp_pool {
   size_t work_cap = 0;
   void* attn_work = nullptr;      // device workspace of the attention call (split-KV partial results)
   size_t attn_work_cap = 0;
+  std::vector<void*> retired;     // outgrown workspace buffers, freed with the pool
   mutable std::mutex mu;          // guards the free lists, the staging slots and the workspace
 };
 

@@ -135,6 +135,7 @@ extern "C" flp_status flp_pool_destroy(flp_pool* p) {
   }
   if (p->work) (void)hipFree(p->work);
   if (p->attn_work) (void)hipFree(p->attn_work);
+  for (void* old : p->retired) (void)hipFree(old);
   if (p->own_dev && p->dev_base) (void)hipFree(p->dev_base);
   if (p->own_host && p->host_base) (void)hipHostFree(p->host_base);
   delete p;
@@ -242,31 +243,30 @@ flp_status flp_stage_release(FlpStageSlot* s, hipStream_t stream) {
   return FLP_OK;
 }
 
-flp_status flp_workspace(flp_pool* p, size_t bytes, void** out) {
-  if (p->work_cap < bytes) {
-    // earlier launches may still be reading the old buffer
-    FLP_TRY_HIP(hipDeviceSynchronize());
-    if (p->work) FLP_TRY_HIP(hipFree(p->work));
-    p->work = nullptr;
-    p->work_cap = 0;
-    size_t cap = (bytes + (1 << 20)) & ~(size_t)((1 << 20) - 1);
-    FLP_TRY_HIP(hipMalloc(&p->work, cap));
-    p->work_cap = cap;
+// Both workspaces only grow, and a buffer that has become too small is not freed before the pool is destroyed:
+// launches enqueued earlier may still read it, and freeing device memory (or waiting for the device) inside a
+// compute call would stall every stream.  Capacities double, so the retired buffers together stay below the live one.
+static flp_status grow(flp_pool* p, void** buf, size_t* cap_now, size_t bytes) {
+  if (*cap_now < bytes) {
+    size_t cap = *cap_now ? *cap_now : ((size_t)1 << 20);
+    while (cap < bytes) cap <<= 1;
+    void* fresh = nullptr;
+    FLP_TRY_HIP(hipMalloc(&fresh, cap));
+    if (*buf) p->retired.push_back(*buf);
+    *buf = fresh;
+    *cap_now = cap;
   }
+  return FLP_OK;
+}
+
+flp_status flp_workspace(flp_pool* p, size_t bytes, void** out) {
+  FLP_TRY(grow(p, &p->work, &p->work_cap, bytes));
   *out = p->work;
   return FLP_OK;
 }
 
 flp_status flp_attn_workspace(flp_pool* p, size_t bytes, void** out) {
-  if (p->attn_work_cap < bytes) {
-    FLP_TRY_HIP(hipDeviceSynchronize());                 // earlier launches may still be reading the old buffer
-    if (p->attn_work) FLP_TRY_HIP(hipFree(p->attn_work));
-    p->attn_work = nullptr;
-    p->attn_work_cap = 0;
-    size_t cap = (bytes + (1 << 20)) & ~(size_t)((1 << 20) - 1);
-    FLP_TRY_HIP(hipMalloc(&p->attn_work, cap));
-    p->attn_work_cap = cap;
-  }
+  FLP_TRY(grow(p, &p->attn_work, &p->attn_work_cap, bytes));
   *out = p->attn_work;
   return FLP_OK;
 }
