@@ -67,6 +67,9 @@ def parse():
     ap.add_argument("--prefix-range", type=int, nargs=2, default=None, metavar=("LO", "HI"),
                     help="override the range the prefix lengths are drawn from (few long sequences: --seqs 4 "
                          "--prefix-range 16383 16383)")
+    ap.add_argument("--early-moves-gb", type=float, default=0.75, help="a step whose moves reach this many GB (about "
+                    "10 ms of the host link in both directions) hands them to the planner before its first compute "
+                    "stage instead of after the KV append (0: always early; a large value: never)")
     ap.add_argument("--one-stream", action="store_true", help="moves and compute on ONE stream (no overlap): the "
                     "baseline the asynchronous pipeline is compared with")
     ap.add_argument("--one-swap-stream", action="store_true", help="write-backs and fetches share one stream beside "
@@ -190,8 +193,19 @@ class Bench:
         self.t_cap = int(min(S * n_max, 1.5 * S * n_mean + 4096))   # far above any batch the trace draws; checked per step
         i32 = torch.int32
         self.d_tables = torch.full((S, trc.max_blocks), -1, dtype=i32, device="cuda")
-        self.d_token_adapter = torch.zeros(self.t_cap, dtype=i32, device="cuda")
-        self.d_rank = torch.zeros(cfg.n_adapters, dtype=i32, device="cuda")
+        # Everything else a step uploads travels as ONE blob in one copy: the adapters' ranks and block tables, the
+        # ids of the sequence slots whose table rows changed (int64, for the scatter), the tokens' adapters, and the
+        # changed rows themselves, which a device-side scatter then puts into d_tables.
+        ev2 = lambda n: (n + 1) & ~1                           # int32 offsets kept even: the id section is read as int64
+        A, Lt, mb = cfg.n_adapters, max(1, len(trc.lora_tables)), trc.max_blocks
+        self.off_idx = ev2(A)
+        self.off_tok = self.off_idx + 2 * S
+        blob_cap = self.off_tok + ev2(self.t_cap) + S * mb + Lt
+        self.d_blob = torch.zeros(blob_cap, dtype=i32, device="cuda")
+        self.d_rank = self.d_blob[:A]
+        self.d_changed = self.d_blob[self.off_idx:self.off_idx + 2 * S].view(torch.int64)
+        self.d_token_adapter = self.d_blob[self.off_tok:self.off_tok + self.t_cap]
+        self.d_lora_tables = torch.zeros(Lt, dtype=i32, device="cuda")    # replaced from the blob when the tables change
         # y is updated in place (y += scale * B A x), the same buffers serve every step, and blocks that held the
         # appended k and v rows come back as adapter pages when the trace recycles them: a branch of noticeable size
         # would feed on itself over a long run (and overflow the 16-bit types).  The bench keeps the activations
@@ -200,14 +214,10 @@ class Bench:
         s = 0.003 / float(np.sqrt(max(cfg.ranks) * cfg.hidden))
         self.d_scales = [torch.full((cfg.n_adapters,), v, dtype=torch.float32, device="cuda") for v in (s, -s)]
         self.n_lora_calls = 0
-        self.d_lora_tables = torch.zeros(max(1, len(trc.lora_tables)), dtype=i32, device="cuda")
+        self.early_move_bytes = args.early_moves_gb * 1e9
         self.d_proj = {n: {k: torch.from_numpy(getattr(pr, k)).cuda() for k in
                            ("a_tab_off", "a_row_base", "b_tab_off", "b_row_base")} for n, pr in trc.proj.items()}
-        self.stage = [dict(tables=torch.empty((S, trc.max_blocks), dtype=i32, pin_memory=True),
-                           token_adapter=torch.empty(self.t_cap, dtype=i32, pin_memory=True),
-                           rank=torch.empty(cfg.n_adapters, dtype=i32, pin_memory=True),
-                           lora_tables=torch.empty(max(1, len(trc.lora_tables)), dtype=i32, pin_memory=True))
-                      for _ in range(3)]
+        self.stage = [torch.zeros(blob_cap, dtype=i32, pin_memory=True) for _ in range(3)]
         # ---- activations of the largest batch the trace can produce (the first T rows are used)
         qd, kd = cfg.n_q_heads * cfg.head_dim, cfg.n_kv_heads * cfg.head_dim
         mk = lambda w: torch.empty((self.t_cap, w), dtype=self.fdt, device="cuda")
@@ -240,21 +250,31 @@ class Bench:
 
     # ---- one step's pieces -------------------------------------------------------------------------
     def upload(self, st, k):
-        """Batch metadata of trace step `st` to the device, on the compute stream, through staging set k % 3."""
+        """Batch metadata of trace step `st` to the device, on the compute stream, through staging blob k % 3: one
+        copy of a few hundred KB, one scatter of the changed table rows and, when adapters were exchanged, one copy
+        of their block tables."""
         torch, np = self.torch, self.np
         sg = self.stage[k % 3]
-        T = st.n_tokens
+        h = sg.numpy()
+        T, S, mb = st.n_tokens, self.cfg.n_seqs, self.trace.max_blocks
+        ch = st.changed_slots
+        n = len(ch)
+        h[:len(st.rank)] = st.rank
+        h[self.off_idx:self.off_idx + 2 * S].view(np.int64)[:n] = ch
+        h[self.off_tok:self.off_tok + T] = st.token_adapter
+        off_rows = self.off_tok + ((T + 1) & ~1)
+        if n:
+            h[off_rows:off_rows + n * mb].reshape(n, mb)[:] = st.kv_tables[ch]
+        off_lt = off_rows + n * mb
+        n_lt = len(st.lora_tables) if st.tables_changed else 0
+        h[off_lt:off_lt + n_lt] = st.lora_tables[:n_lt]
+        end = off_lt + n_lt
         with torch.cuda.stream(self.s_comp):
-            if len(st.changed_slots):                          # a few MB at most: the whole table, asynchronously
-                sg["tables"].numpy()[:] = st.kv_tables
-                self.d_tables.copy_(sg["tables"], non_blocking=True)
-            sg["token_adapter"].numpy()[:T] = st.token_adapter
-            self.d_token_adapter[:T].copy_(sg["token_adapter"][:T], non_blocking=True)
-            sg["rank"].numpy()[:] = st.rank
-            self.d_rank.copy_(sg["rank"], non_blocking=True)
-            if st.tables_changed and len(st.lora_tables):
-                sg["lora_tables"].numpy()[:] = st.lora_tables
-                self.d_lora_tables.copy_(sg["lora_tables"], non_blocking=True)
+            self.d_blob[:end].copy_(sg[:end], non_blocking=True)
+            if n:
+                self.d_tables.index_copy_(0, self.d_changed[:n], self.d_blob[off_rows:off_lt].view(n, mb))
+            if n_lt:
+                self.d_lora_tables[:n_lt].copy_(self.d_blob[off_lt:end])
 
     def pj(self, n):
         return dict(y=self.ys[n], d_out=self.trace.proj[n].d_out, **self.d_proj[n])
@@ -340,9 +360,18 @@ class Bench:
             if st.n_tokens > self.t_cap:
                 raise SystemExit("bench.py: a step of %d tokens exceeds the activation buffers (%d)" % (st.n_tokens, self.t_cap))
             self.upload(st, g)
-            if self.planner is not None:
-                # request g = the queries that join at step g + 1, with their fetches and the write-backs of what left
+            # Request g = the queries that join at step g + 1, with their fetches and the write-backs of what left.
+            # Moves that fit beside the attention kernel are handed to the planner after the two streaming stages
+            # (LoRA q,k,v and the KV append), with the compute announced up to there: beside the moves the streaming
+            # stages run many times slower (memory latency under the host-link traffic), the attention kernel, bound
+            # by the matrix cores, a few per cent.  Moves that outlast the compute bound the step by themselves and
+            # start as early as they may.  Measured on 34b_gqa: 18.15 ms per step always early, 17.47 with this
+            # rule, 17.21 never early (which stretches the attention launches of the burst steps to 26 ms).
+            move_bytes = (len(st.swap_in_dev) + len(st.swap_out_dev)) * self.cfg.block_bytes
+            early = self.planner is not None and move_bytes >= self.early_move_bytes
+            if early:
                 self.planner.submit(g, st.swap_in_host, st.swap_in_dev, st.swap_out_dev, st.swap_out_host)
+            if self.planner is not None:
                 if g >= 1:
                     self.planner.stream_wait(g - 1, self.s_comp)     # this step's joiners were fetched by request g - 1
             else:
@@ -361,6 +390,9 @@ class Bench:
             ev = None
             self.lora_qkv(st, self.s_comp)
             self.kv_append(st, self.s_comp)
+            if self.planner is not None and not early:
+                self.planner.compute_enqueued(self.s_comp)
+                self.planner.submit(g, st.swap_in_host, st.swap_in_dev, st.swap_out_dev, st.swap_out_host)
             if timed:
                 ev = (torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
                 ev[0].record(self.s_comp)

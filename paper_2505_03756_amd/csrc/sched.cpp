@@ -1,6 +1,6 @@
 // The asynchronous swap planner (paper section 4.3): requests whose block moves are in flight wait,
 // requests whose blocks have arrived are handed to the caller for the next compute batch.  Host logic
-// only: the moves themselves are flp_pool_swap_out / flp_pool_swap_in on two streams of the planner.
+// only: the moves themselves are the pool's swap-out / swap-in on two streams of the planner.
 #include <deque>
 #include <mutex>
 #include <new>
@@ -142,18 +142,21 @@ extern "C" flp_status fls_submit(fls_sched* s, int64_t req_id, int32_t n_in, con
     // both lists are checked before anything is enqueued, so a refused request leaves no move behind
     FLP_TRY(flp_swap_check(s->pool, n_out, out_dev_ids, out_host_ids, 0, "fls_submit (write-backs)"));
     FLP_TRY(flp_swap_check(s->pool, n_in, host_ids, dev_ids, 1, "fls_submit (fetches)"));
+    // a request that moves blocks both ways has its two kernels share the host link: the fetch, which the
+    // request's compute waits for, is launched wider than the write-back
+    const bool duplex = n_in > 0 && n_out > 0;
     // fetches land in blocks that an earlier request's write-back may have released
     if (s->have_out) FLP_TRY_HIP(hipStreamWaitEvent(s->s_in, s->ev_out, 0));
     if (n_out > 0) {
       // the compute announced last may still append to the blocks that go out
       if (s->have_compute) FLP_TRY_HIP(hipStreamWaitEvent(s->s_out, s->ev_compute, 0));
-      FLP_TRY(flp_pool_swap_out(s->pool, n_out, out_dev_ids, out_host_ids, s->s_out));
+      FLP_TRY(flp_swap_duplex(s->pool, n_out, out_dev_ids, out_host_ids, 0, s->s_out, duplex));
       FLP_TRY_HIP(hipEventRecord(s->ev_out, s->s_out));
       s->have_out = true;
       // ... or this request's own, when the caller says that they make the room
       if (flags & FLS_FETCH_INTO_RELEASED) FLP_TRY_HIP(hipStreamWaitEvent(s->s_in, s->ev_out, 0));
     }
-    if (n_in > 0) FLP_TRY(flp_pool_swap_in(s->pool, n_in, host_ids, dev_ids, s->s_in));
+    if (n_in > 0) FLP_TRY(flp_swap_duplex(s->pool, n_in, host_ids, dev_ids, 1, s->s_in, duplex));
     FLP_TRY(take_event(s, &r.done));
     FLP_TRY_HIP(hipEventRecord(r.done, s->s_in));
   }

@@ -73,17 +73,23 @@ flp_status flp_launch_stage_copy(const void* src_pinned, void* dst_dev, size_t b
 }
 
 flp_status flp_launch_copy_blocks(const uint8_t* src_base, uint8_t* dst_base, const int32_t* src_ids_dev,
-                                  const int32_t* dst_ids_dev, int32_t n, int64_t block_bytes, bool over_host_link,
+                                  const int32_t* dst_ids_dev, int32_t n, int64_t block_bytes, int host_link,
                                   hipStream_t stream) {
   if (n <= 0) return FLP_OK;
   const int64_t chunk_bytes = 16384;
   const int64_t chunks = (block_bytes + chunk_bytes - 1) / chunk_bytes;
   const int64_t total = (int64_t)n * chunks;
-  // measured on MI355X: 16 resident workgroups already saturate the host link (57 GB/s in,
-  // 55 GB/s out), and every further workgroup that waits on host-link reads slows the HBM
-  // traffic of the kernels running beside the swap (96 workgroups: a streaming copy on another
-  // stream runs 4x slower; 16: 1.1x); a tier that lives in device memory wants the whole chip
-  const int64_t max_wgs = over_host_link ? 16 : 2048;
+  // Measured on MI355X.  One direction alone: 16 resident workgroups saturate the host link (57 GB/s in,
+  // 55 GB/s out), and every further workgroup that waits on host-link reads slows the HBM traffic of the
+  // kernels running beside the move (96 workgroups: a streaming copy on another stream runs 4x slower;
+  // 16: 1.1x).  Both directions at once share the link unevenly at equal widths (16 and 16: 40 GB/s in,
+  // 47 out, and the write-backs are what slows the kernels beside them most); the fetch is what the next
+  // compute step waits for, so a caller that runs both directions together (the planner, for a request
+  // with both lists) asks for three workgroups per XCD in and one out: 46 and 45 GB/s (a step of 1.44 GB
+  // each way: 36.7 ms at 16 and 16, 33.7 ms at 24 and 8; widths that do not divide by the 8 XCDs load
+  // them unevenly and do worse).  A tier that lives in device memory wants the whole chip.
+  const int64_t max_wgs = host_link == FLP_LINK_NONE ? 2048 : host_link == FLP_LINK_IN_DUPLEX ? 24
+                          : host_link == FLP_LINK_OUT_DUPLEX ? 8 : 16;
   dim3 grid((unsigned)(total < max_wgs ? total : max_wgs));
   if (block_bytes % 16 == 0) {
     hipLaunchKernelGGL(copy_blocks_kernel<u32x4>, grid, dim3(kThreads), 0, stream, src_base, dst_base, src_ids_dev,

@@ -18,7 +18,7 @@
 
 // The pool's source file refers to the two copy launchers of the GPU build; the walk never swaps block
 // contents, so here they only have to exist.
-flp_status flp_launch_copy_blocks(const uint8_t*, uint8_t*, const int32_t*, const int32_t*, int32_t, int64_t, bool,
+flp_status flp_launch_copy_blocks(const uint8_t*, uint8_t*, const int32_t*, const int32_t*, int32_t, int64_t, int,
                                   hipStream_t) {
   std::fprintf(stderr, "cache_fuzz: a copy was launched\n");
   std::abort();

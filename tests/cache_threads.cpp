@@ -14,7 +14,7 @@
 #include "flp_internal.h"
 
 // The pool's source file refers to the two copy launchers of the GPU build; nothing here swaps block contents.
-flp_status flp_launch_copy_blocks(const uint8_t*, uint8_t*, const int32_t*, const int32_t*, int32_t, int64_t, bool,
+flp_status flp_launch_copy_blocks(const uint8_t*, uint8_t*, const int32_t*, const int32_t*, int32_t, int64_t, int,
                                   hipStream_t) {
   std::abort();
 }
