@@ -84,6 +84,9 @@ def parse():
     ap.add_argument("--calibrate-copy", action="store_true", help="run only a plain block copy of 1 GiB through "
                     "flp_pool_swap_in between two device tiers (the kernel of known traffic that scales the "
                     "rocprofv3 FETCH_SIZE / WRITE_SIZE readings) and exit")
+    ap.add_argument("--attention-clock", type=float, default=None, metavar="SECONDS", help="run only the attention "
+                    "stage of one batch of the workload in a loop for SECONDS while rocm-smi samples the shader "
+                    "clock, on the pool as drawn and then on a zeroed pool, and print the two rates and clocks")
     ap.add_argument("--seed", type=int, default=None)
     return ap.parse_args()
 
@@ -623,6 +626,8 @@ def main():
     torch.cuda.set_device(0)
     if args.calibrate_copy:
         return calibrate_copy()
+    if args.attention_clock is not None:
+        return attention_clock(args)
     names = [args.workload] if args.workload else list(WORKLOADS)
     out = None
     for i, name in enumerate(names):
@@ -671,6 +676,71 @@ def achievable_rates(stream):
     return {"hbm_copy_GBps": round(2 * n_dev / (t_copy * 1e6), 1), "pcie_h2d_GBps": round(n_host / (t_h2d * 1e6), 1),
             "note": "1 GiB device-to-device copy (read + write bytes) and 512 MiB pinned host-to-device copy by the "
                     "runtime's copy routines, median of 5"}
+
+
+def attention_clock(args):
+    """The attention stage alone, back to back for some seconds, with the shader clock sampled from rocm-smi beside
+    it: on the pool as drawn (N(0,1) keys and values) and on a zeroed pool.  The instruction stream is the same in
+    both phases; what differs is the power the matrix cores draw, and with it the clock the chip holds."""
+    import re
+    import subprocess
+    import threading
+    import numpy as np
+    import torch
+    name = args.workload or WORKLOADS[0]
+    b = Bench(name, args)
+    b.reset_pipeline()
+    recs = b.run(3, timed=False)
+    torch.cuda.synchronize()
+    st = recs[-1]["st"]
+    flops = b.work(st)["attn_flops"]
+    samples, stop = [], threading.Event()
+
+    def sampler():
+        while not stop.is_set():
+            try:
+                r = subprocess.run(["/opt/rocm/bin/rocm-smi", "--showclocks", "--csv"], capture_output=True, text=True,
+                                   timeout=10)
+                m = re.findall(r"\((\d+)Mhz\)", r.stdout.strip().splitlines()[-1])
+                if m:
+                    samples.append((time.time(), int(m[-1])))      # the last clock of the row is sclk
+            except (OSError, subprocess.SubprocessError, IndexError):
+                pass
+            time.sleep(0.25)
+
+    th = threading.Thread(target=sampler)
+    th.start()
+    out = {"workload": name, "tokens": st.n_tokens, "flops_per_launch": flops, "phases": []}
+    try:
+        for phase in ("pool as drawn", "pool zeroed"):
+            if phase == "pool zeroed":
+                b.dev.zero_()
+            for _ in range(3):
+                b.attention(st, b.s_comp)
+            torch.cuda.synchronize()
+            t0, ms = time.time(), []
+            while time.time() - t0 < args.attention_clock:
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record(b.s_comp)
+                for _ in range(5):
+                    b.attention(st, b.s_comp)
+                e1.record(b.s_comp)
+                torch.cuda.synchronize()
+                ms.append(e0.elapsed_time(e1) / 5)
+            t1 = time.time()
+            clk = [c for t, c in samples if t0 + 1.0 <= t <= t1]
+            out["phases"].append({"data": phase, "launches": 5 * len(ms), "ms_per_launch": round(float(np.mean(ms)), 4),
+                                  "TFLOPps": round(flops / float(np.mean(ms)) / 1e9, 1),
+                                  "sclk_MHz_median": float(np.median(clk)) if clk else None,
+                                  "sclk_MHz_min_max": [min(clk), max(clk)] if clk else None, "sclk_samples": len(clk)})
+            time.sleep(1.5)
+    finally:
+        stop.set()
+        th.join()
+    idle = [c for t, c in samples[-4:]]
+    out["sclk_MHz_idle_after"] = idle
+    print(json.dumps(out))
+    b.close()
 
 
 def calibrate_copy():
