@@ -35,6 +35,7 @@ HBM_PEAK_GBS = 8000.0        # MI355X HBM3E, published
 MFMA_PEAK_TFLOPS = 2500.0    # dense fp16 / bf16 MFMA, published
 FP32_PEAK_TFLOPS = 157.3     # fp32 vector, published
 PCIE_PEAK_GBS = 64.0         # PCIe Gen5 x16, one direction
+_COMPUTE_STREAM = None
 WORKLOADS = ("34b_gqa", "13b", "7b_prefill", "7b_decode", "tiny")
 # HBM bytes per launch of a workload's dominant kernel, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this
 # file, scaled by what the same counters read for a plain copy of known size: profiles/measured_traffic.json.
@@ -236,7 +237,12 @@ class Bench:
         self.max_rank = int(max(cfg.ranks))
         # default priority, all three.  The two directions of the host link are independent: write-backs and
         # fetches get a stream each.
-        self.s_comp = torch.cuda.Stream()
+        # One compute stream for the life of the process (a workload after the first would otherwise get a stream
+        # that the runtime may bind to the hardware queue of a move stream, where the two take turns).
+        global _COMPUTE_STREAM
+        if _COMPUTE_STREAM is None:
+            _COMPUTE_STREAM = torch.cuda.Stream()
+        self.s_comp = _COMPUTE_STREAM
         self.planner = None
         if args.one_stream:
             self.s_in = self.s_out = self.s_comp
@@ -499,6 +505,7 @@ def run_workload(name, args, headline):
     t_hbm, t_mfma = a_bytes / (HBM_PEAK_GBS * 1e9), a_flops / (MFMA_PEAK_TFLOPS * 1e12)
     traffic = measured_traffic(cfg.name, kname, ksrc) if not b.over and args.swap_frac is None else None
     common = {"traffic": traffic, "kernel": kname, "launches_timed": len(attn_ms), "avg_launch_ms": round(a_ms, 4),
+              "median_launch_ms": round(float(np.median(attn_ms)), 4),
               "algorithmic_bytes_per_launch": int(a_bytes), "algorithmic_flops_per_launch": int(a_flops),
               "measured": "HIP events around the kernel's launches on the compute stream inside the timed region "
                           "(moves running beside it)"}
@@ -553,6 +560,12 @@ def run_workload(name, args, headline):
             den = ach["pcie_h2d_GBps"] if kk["bound"] == "pcie" else ach["hbm_copy_GBps"]
             kk["frac_of_achievable"] = round(kk["GBps"] / den, 4)
     compute_ms = sum(v for k2, v in stage_ms.items() if k2 != "swap")
+    # the same kernel with nothing beside it (serialised pass, last batch), for the reader of `frac`: in a step that the
+    # host link bounds the launches of the timed region run beside both move kernels and are stretched by them
+    ka = kernels["attention"]
+    roof["alone_ms_last_batch"] = ka["ms"]
+    roof["frac_alone_last_batch"] = round((ka["TFLOPps"] / MFMA_PEAK_TFLOPS) if roof["bound"] == "mfma"
+                                          else (ka["GBps"] / HBM_PEAK_GBS), 4)
     trc = b.trace
     n_in = [len(r["st"].swap_in_dev) for r in recs]
     n_out = [len(r["st"].swap_out_dev) for r in recs]

@@ -27,7 +27,11 @@
  *   fls_compute_enqueued  the caller has enqueued a batch's compute on `compute_stream`; later
  *                       write-backs are ordered after it.
  *
- * A planner created with `manual = 1` issues nothing and owns no streams: requests complete when the
+ * The in and out streams belong to the device, not to the planner: they are created with the device's
+ * first planner and kept for the life of the process, and all planners on a device share them (their
+ * moves are then ordered among each other as well, which is harmless).
+ *
+ * A planner created with `manual = 1` issues nothing and uses no streams: requests complete when the
  * caller says so (fls_complete).  It is the same policy as a discrete-event model, for simulations of
  * arrival patterns on the host and for the tests of the policy itself.
  *
