@@ -29,7 +29,8 @@
  *
  * The in and out streams belong to the device, not to the planner: they are created with the device's
  * first planner and kept for the life of the process, and all planners on a device share them (their
- * moves are then ordered among each other as well, which is harmless).
+ * moves are then ordered among each other as well, which is harmless).  fls_create wants the pool's
+ * device current (FLP_EHIP otherwise).
  *
  * A planner created with `manual = 1` issues nothing and uses no streams: requests complete when the
  * caller says so (fls_complete).  It is the same policy as a discrete-event model, for simulations of

@@ -80,14 +80,15 @@ flp_status is_ready(const Request& r, bool* ready) {
 // get queues of their own, streams made later (a second planner after the first was destroyed) have been seen to
 // land on the compute stream's queue, where moves and compute take turns instead of overlapping (a step bound by
 // its fetches: 9.2 ms instead of 8.0).  Both streams have the default priority.
-static hipError_t move_streams(hipStream_t* s_in, hipStream_t* s_out) {
+static hipError_t move_streams(int pool_device, hipStream_t* s_in, hipStream_t* s_out) {
   constexpr int kMaxDevices = 64;
   static std::mutex mu;
   static hipStream_t streams[kMaxDevices][2];
   int dev = 0;
   hipError_t e = hipGetDevice(&dev);
   if (e != hipSuccess) return e;
-  if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+  // streams belong to the device that is current when they are made: it has to be the pool's
+  if (dev < 0 || dev >= kMaxDevices || (pool_device >= 0 && dev != pool_device)) return hipErrorInvalidDevice;
   std::lock_guard<std::mutex> lk(mu);
   for (int i = 0; i < 2; ++i)
     if (!streams[dev][i]) {
@@ -116,7 +117,7 @@ extern "C" flp_status fls_create(flp_pool* pool, int32_t manual, fls_sched** out
   s->pool = pool;
   s->manual = manual != 0;
   if (!s->manual) {
-    hipError_t e = move_streams(&s->s_in, &s->s_out);
+    hipError_t e = move_streams(pool->device, &s->s_in, &s->s_out);
     if (e == hipSuccess) e = hipEventCreateWithFlags(&s->ev_compute, hipEventDisableTiming);
     if (e == hipSuccess) e = hipEventCreateWithFlags(&s->ev_out, hipEventDisableTiming);
     if (e != hipSuccess) {
