@@ -109,3 +109,38 @@ def test_planner_driven_run_equals_the_all_resident_run(seed, dtype, gqa):
     print("\n[planner] %d batches of sizes %s, %d polls (%d empty)" % (len(batches), batches, stats["polls"],
                                                                     stats["polls_empty"]), flush=True)
     plan.close()
+
+
+def test_planners_of_a_device_share_its_move_streams():
+    """The move streams belong to the device: a second planner, and one made after the first was destroyed, move
+    blocks correctly (fetches, write-backs, both in one request) and byte for byte."""
+    import torch
+    cfg = wl.LayerConfig("sched2", "f16", 512, 4, 4, 128, 600, 600, 4, (8,), ("q",), 2, (30, 60), (1, 8), seed=77)
+    rng = np.random.default_rng(9)
+    dev = wl.quantize(rng.standard_normal((cfg.n_dev_blocks, cfg.block_elems)).astype(np.float32), "f16")
+    host = wl.quantize(rng.standard_normal((cfg.n_host_blocks, cfg.block_elems)).astype(np.float32), "f16")
+    from paper_2505_03756_amd.harness import GpuPool
+    gp = GpuPool(cfg, dev, host)
+    want_dev, want_host = dev.copy(), host.copy()
+    a, b = flsched.Planner(gp.pool), flsched.Planner(gp.pool)
+    ids = rng.permutation(600).astype(np.int32)
+    req = 0
+    for plan, lo in ((a, 0), (b, 100), (a, 200)):
+        hin, din = ids[lo:lo + 40], ids[lo + 40:lo + 80]
+        dout, hout = ids[lo + 80:lo + 90], ids[lo + 90:lo + 100]
+        want_host[hout] = want_dev[dout]
+        want_dev[din] = want_host[hin]
+        plan.submit(req, hin, din, dout, hout)
+        req += 1
+    a.wait_next(), b.wait_next()
+    torch.cuda.synchronize()
+    a.close()
+    c = flsched.Planner(gp.pool)                                   # made after a planner of the device was destroyed
+    hin, din = ids[400:440], ids[440:480]
+    want_dev[din] = want_host[hin]
+    c.submit(req, hin, din)
+    c.wait_next()
+    torch.cuda.synchronize()
+    assert np.array_equal(to_np(gp.dev, gp.sd), want_dev)
+    assert np.array_equal(to_np(gp.host, gp.sd), want_host)
+    b.close(), c.close()
