@@ -794,7 +794,8 @@ flp_status launch_pair(const FlpLoraArgs& a, const FlpLoraMfma& c, hipStream_t s
     if (a.d_in % 64 == 0) {
       // two rank tiles: the projections of a call with two or three of them are fused (13B shapes, q,k,v call:
       // 0.89 -> 0.86 ms); with four rank tiles the fused stages leave one workgroup per CU and the call takes
-      // twice as long (34B shapes: 1.25 -> 2.35 ms), so there a workgroup keeps to one projection
+      // twice as long (34B shapes: 1.25 -> 2.35 ms; the same with a ring of four stages in 128 KiB of dynamic LDS: 1.35 ->
+      // 2.38 ms), so there a workgroup keeps to one projection
       constexpr int NPJ2 = NT == 2 ? 2 : 1, NPJ3 = NT == 2 ? 3 : 1;
       const dim3 gf((unsigned)(c.tiles_grid * c.k_splits));
       if (NT == 2 && a.n_proj == 2)
