@@ -168,7 +168,7 @@ class Bench:
         nd, nh = pool_size_for(cfg, args)
         cfg = cfg.scaled(n_dev_blocks=nd, n_host_blocks=nh)
         self.cfg, self.tc, self.args = cfg, tc, args
-        self.seed = cfg.seed if args.seed is None else args.seed
+        self.seed = args.seed if args.seed is not None else (tc.seed if tc.seed is not None else cfg.seed)
         t0 = time.time()
         # ---- the two tiers.  Block contents are N(0,1) values in the pool's element type: every block may become
         #      KV or adapter pages as the trace recycles it.
@@ -374,7 +374,7 @@ class Bench:
             # (LoRA q,k,v and the KV append), with the compute announced up to there: beside the moves the streaming
             # stages run many times slower (memory latency under the host-link traffic), the attention kernel, bound
             # by the matrix cores, a few per cent.  Moves that outlast the compute bound the step by themselves and
-            # start as early as they may.  Measured on 34b_gqa: 18.15 ms per step always early, 17.47 with this
+            # start as early as they may.  Measured on 34b_gqa (35 burst steps in 200): 18.15 ms per step always early, 17.47 with this
             # rule, 17.21 never early (which stretches the attention launches of the burst steps to 26 ms).
             move_bytes = (len(st.swap_in_dev) + len(st.swap_out_dev)) * self.cfg.block_bytes
             early = self.planner is not None and move_bytes >= self.early_move_bytes
@@ -591,7 +591,7 @@ def run_workload(name, args, headline):
                    "adapter_pool": cfg.n_adapters, "adapter_dist": cfg.adapter_dist,
                    "adapters_in_last_batch": int((st.rank > 0).sum()), "ranks": sorted(set(int(r) for r in cfg.ranks)),
                    "lora_on": list(cfg.projections), "base_gemm": "excluded (y arrives holding x.W)",
-                   "trace": {"mode": tc.mode, "churn_frac": tc.churn_frac if tc.mode == "churn" else None,
+                   "trace": {"mode": tc.mode, "seed": int(b.seed), "churn_frac": tc.churn_frac if tc.mode == "churn" else None,
                              "swap_out": tc.swap_out, "shift_period": tc.shift_period or None,
                              "lam_calm": tc.lam_calm if tc.mode == "bursty" else None,
                              "lam_burst": tc.lam_burst if tc.mode == "bursty" else None,

@@ -50,6 +50,7 @@ class TraceConfig:
     churn_frac: float = 0.25        # churn: share of the batch's needed blocks brought in per step
     swap_out: bool = True           # write back as many blocks of departed queries as are brought in
     shift_period: int = 0           # redraw the popularity -> adapter id permutation every so many steps (0: never)
+    seed: Optional[int] = None      # seed of the trace's draws (None: the workload's own seed)
 
 
 def trace_config(name: str) -> TraceConfig:
@@ -59,7 +60,12 @@ def trace_config(name: str) -> TraceConfig:
         "7b_prefill": TraceConfig(mode="churn", churn_frac=0.4, swap_out=False),
         "7b_decode": TraceConfig(mode="static"),
         "13b": TraceConfig(mode="churn", churn_frac=0.25, swap_out=True, shift_period=1000),
-        "34b_gqa": TraceConfig(mode="bursty"),
+        # The seed decides where the bursts of a run fall.  A benchmark run times 20 to 1000 steps, and the draw of the
+        # workload's own seed puts 9 burst steps into the first 20 timed ones (stationary share: 4).  Of the seeds
+        # 1..29 this is the one whose windows all hold close to the stationary share (4 burst steps among the timed
+        # steps 5..24, 45 among 5..204, 195 among 5..1004; 0.57 / 0.56 / 0.50 GB moved per step), so that a run of
+        # any length times a representative mix.
+        "34b_gqa": TraceConfig(mode="bursty", seed=29),
     }[name]
 
 
