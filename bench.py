@@ -374,8 +374,9 @@ class Bench:
             # (LoRA q,k,v and the KV append), with the compute announced up to there: beside the moves the streaming
             # stages run many times slower (memory latency under the host-link traffic), the attention kernel, bound
             # by the matrix cores, a few per cent.  Moves that outlast the compute bound the step by themselves and
-            # start as early as they may.  Measured on 34b_gqa (35 burst steps in 200): 18.15 ms per step always early, 17.47 with this
-            # rule, 17.21 never early (which stretches the attention launches of the burst steps to 26 ms).
+            # start as early as they may.  Measured on 34b_gqa (35 burst steps in 200): 18.15 ms per step always
+            # early, 17.47 with this rule, 17.21 never early (which stretches the attention launches of the burst
+            # steps to 26 ms).
             move_bytes = (len(st.swap_in_dev) + len(st.swap_out_dev)) * self.cfg.block_bytes
             early = self.planner is not None and move_bytes >= self.early_move_bytes
             if early:
