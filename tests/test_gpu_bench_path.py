@@ -19,7 +19,7 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 CASES = [
     # workload, overrides, steps before the checked one, sampled tokens
     ("7b_prefill", ["--seqs", "6", "--dev-blocks", "4096", "--host-blocks", "2048"], 3, 96),
-    ("34b_gqa", ["--seqs", "24", "--dev-blocks", "49152", "--host-blocks", "16384"], 4, 64),
+    ("34b_gqa", ["--seqs", "24", "--dev-blocks", "49152", "--host-blocks", "65536"], 4, 64),
     ("7b_decode", ["--seqs", "24", "--dev-blocks", "8192", "--host-blocks", "64"], 2, 24),
     ("tiny", [], 3, 64),
 ]
