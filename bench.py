@@ -71,6 +71,9 @@ def parse():
     ap.add_argument("--early-moves-gb", type=float, default=0.75, help="a step whose moves reach this many GB (about "
                     "10 ms of the host link in both directions) hands them to the planner before its first compute "
                     "stage instead of after the KV append (0: always early; a large value: never)")
+    ap.add_argument("--no-narrow-moves", action="store_true", help="never flag a request as unhurried (by default a "
+                    "request handed over after the KV append whose moves need less than half a step at the narrow "
+                    "rate is: the planner then launches its moves narrow)")
     ap.add_argument("--one-stream", action="store_true", help="moves and compute on ONE stream (no overlap): the "
                     "baseline the asynchronous pipeline is compared with")
     ap.add_argument("--one-swap-stream", action="store_true", help="write-backs and fetches share one stream beside "
@@ -361,6 +364,7 @@ class Bench:
         torch = self.torch
         recs = []
         one = self.args.one_stream
+        self.t_prev = None                                   # a pause between two calls is no step
         for k in range(n_steps):
             g = self.step_no
             if g >= 2:
@@ -402,7 +406,12 @@ class Bench:
             self.kv_append(st, self.s_comp)
             if self.planner is not None and not early:
                 self.planner.compute_enqueued(self.s_comp)
-                self.planner.submit(g, st.swap_in_host, st.swap_in_dev, st.swap_out_dev, st.swap_out_host)
+                # moves that need less than half of a step's time at the narrow rate (about 60 GB/s) are flagged as
+                # unhurried: the planner launches them narrow and the attention kernel beside them keeps its pace
+                unhurried = (not self.args.no_narrow_moves and self.step_est is not None
+                             and move_bytes / 60e9 < 0.5 * self.step_est)
+                self.planner.submit(g, st.swap_in_host, st.swap_in_dev, st.swap_out_dev, st.swap_out_host,
+                                    unhurried=unhurried)
             if timed:
                 ev = (torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
                 ev[0].record(self.s_comp)
@@ -417,11 +426,17 @@ class Bench:
             if self.planner is not None:
                 self.planner.compute_enqueued(self.s_comp)
             self.step_no += 1
-            recs.append(dict(st=st, ev=ev, t_host=time.perf_counter()))
+            now = time.perf_counter()
+            if self.t_prev is not None and g >= 3:           # the host runs two steps ahead, then at the GPU's pace
+                dt = now - self.t_prev
+                self.step_est = dt if self.step_est is None else 0.8 * self.step_est + 0.2 * dt
+            self.t_prev = now
+            recs.append(dict(st=st, ev=ev, t_host=now))
         return recs
 
     def reset_pipeline(self):
         self.step_no, self.prev_comp, self.prev_in, self.prev_out, self.comp_done = 0, None, None, None, [None] * 3
+        self.t_prev, self.step_est = None, None             # host-side estimate of the time a step takes (seconds)
 
     def close(self):
         """Give the card back: the next workload sizes its pool by what is free."""

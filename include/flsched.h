@@ -62,10 +62,12 @@ flp_status fls_create(flp_pool* pool, int32_t manual, fls_sched** out);
 flp_status fls_destroy(fls_sched* s);
 
 #define FLS_FETCH_INTO_RELEASED 1   /* the fetches land in blocks that this request's write-backs release */
+#define FLS_UNHURRIED 2             /* the moves have a whole compute step to finish in: they are launched narrow, so that
+                                       the kernels running beside them lose less (at about two thirds of the link's rate) */
 
 /* host_ids / dev_ids: n_in pairs for flp_pool_swap_in; out_dev_ids / out_host_ids: n_out pairs for
  * flp_pool_swap_out.  Host arrays, consumed before the call returns.  A request without moves is ready
- * at once.  flags: 0 or FLS_FETCH_INTO_RELEASED. */
+ * at once.  flags: 0 or a combination of FLS_FETCH_INTO_RELEASED and FLS_UNHURRIED. */
 flp_status fls_submit(fls_sched* s, int64_t req_id, int32_t n_in, const int32_t* host_ids, const int32_t* dev_ids,
                       int32_t n_out, const int32_t* out_dev_ids, const int32_t* out_host_ids, int32_t flags);
 /* Up to `max` ready requests, oldest first; they leave the planner.  *n_ready may be 0. */

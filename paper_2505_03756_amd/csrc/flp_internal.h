@@ -97,11 +97,14 @@ flp_status flp_static_scratch_setup(int device, void** out);
 flp_status flp_launch_copy_blocks(const uint8_t* src_base, uint8_t* dst_base, const int32_t* src_ids_dev,
                                   const int32_t* dst_ids_dev, int32_t n, int64_t block_bytes,
                                   int host_link, hipStream_t stream);
-// host_link: which side of the copy is the pinned host tier, and whether the caller runs the other direction beside it
-enum { FLP_LINK_NONE = 0, FLP_LINK_IN = 1, FLP_LINK_OUT = 2, FLP_LINK_IN_DUPLEX = 3, FLP_LINK_OUT_DUPLEX = 4 };
-// flp_pool_swap_in / flp_pool_swap_out (src_tier 1 / 0) for a caller that issues both directions together
+// host_link: which side of the copy is the pinned host tier, and how wide the caller wants the launch
+enum { FLP_LINK_NONE = 0, FLP_LINK_IN = 1, FLP_LINK_OUT = 2, FLP_LINK_IN_DUPLEX = 3, FLP_LINK_OUT_DUPLEX = 4,
+       FLP_LINK_IN_NARROW = 5, FLP_LINK_OUT_NARROW = 6 };
+// flp_pool_swap_in / flp_pool_swap_out (src_tier 1 / 0) for a caller that knows what runs beside the move: one
+// direction alone, both directions together, or moves that need not hurry
+enum { FLP_WIDTH_SINGLE = 0, FLP_WIDTH_DUPLEX = 1, FLP_WIDTH_NARROW = 2 };
 flp_status flp_swap_duplex(flp_pool* p, int32_t n, const int32_t* src_ids, const int32_t* dst_ids, int src_tier,
-                           void* hip_stream, bool duplex);
+                           void* hip_stream, int width);
 
 flp_status flp_launch_stage_copy(const void* src_pinned, void* dst_dev, size_t bytes, hipStream_t stream);
 

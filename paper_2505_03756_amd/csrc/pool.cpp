@@ -307,7 +307,7 @@ flp_status flp_swap_check(flp_pool* p, int32_t n, const int32_t* src_ids, const 
 }
 
 static flp_status swap_common(flp_pool* p, int32_t n, const int32_t* src_ids, const int32_t* dst_ids,
-                              int src_tier, void* hip_stream, const char* who, bool duplex = false) {
+                              int src_tier, void* hip_stream, const char* who, int width = FLP_WIDTH_SINGLE) {
   if (!p || n < 0 || (n > 0 && (!src_ids || !dst_ids))) {
     flp_set_error("%s: invalid argument", who);
     return FLP_EINVAL;
@@ -329,16 +329,20 @@ static flp_status swap_common(flp_pool* p, int32_t n, const int32_t* src_ids, co
   const int32_t* d = (const int32_t*)slot->dev;
   flp_status st = flp_launch_copy_blocks(src_base, dst_base, d, d + n, n, p->block_bytes,
                                          p->host_tier_in_hbm ? FLP_LINK_NONE
-                                         : src_tier == 1   ? (duplex ? FLP_LINK_IN_DUPLEX : FLP_LINK_IN)
-                                                           : (duplex ? FLP_LINK_OUT_DUPLEX : FLP_LINK_OUT),
+                                         : src_tier == 1   ? (width == FLP_WIDTH_DUPLEX   ? FLP_LINK_IN_DUPLEX
+                                                              : width == FLP_WIDTH_NARROW ? FLP_LINK_IN_NARROW
+                                                                                          : FLP_LINK_IN)
+                                                           : (width == FLP_WIDTH_DUPLEX   ? FLP_LINK_OUT_DUPLEX
+                                                              : width == FLP_WIDTH_NARROW ? FLP_LINK_OUT_NARROW
+                                                                                          : FLP_LINK_OUT),
                                          stream);
   flp_status st2 = flp_stage_release(slot, stream);
   return st != FLP_OK ? st : st2;
 }
 
 flp_status flp_swap_duplex(flp_pool* p, int32_t n, const int32_t* src_ids, const int32_t* dst_ids, int src_tier,
-                           void* hip_stream, bool duplex) {
-  return swap_common(p, n, src_ids, dst_ids, src_tier, hip_stream, src_tier == 1 ? "fetch" : "write-back", duplex);
+                           void* hip_stream, int width) {
+  return swap_common(p, n, src_ids, dst_ids, src_tier, hip_stream, src_tier == 1 ? "fetch" : "write-back", width);
 }
 
 extern "C" flp_status flp_pool_swap_in(flp_pool* p, int32_t n, const int32_t* host_ids, const int32_t* dev_ids,

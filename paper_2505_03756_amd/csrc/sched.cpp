@@ -148,7 +148,7 @@ extern "C" flp_status fls_destroy(fls_sched* s) {
 extern "C" flp_status fls_submit(fls_sched* s, int64_t req_id, int32_t n_in, const int32_t* host_ids,
                                  const int32_t* dev_ids, int32_t n_out, const int32_t* out_dev_ids,
                                  const int32_t* out_host_ids, int32_t flags) {
-  if (!s || n_in < 0 || n_out < 0 || (flags & ~FLS_FETCH_INTO_RELEASED) || (n_in > 0 && (!host_ids || !dev_ids)) || (n_out > 0 && (!out_dev_ids || !out_host_ids))) {
+  if (!s || n_in < 0 || n_out < 0 || (flags & ~(FLS_FETCH_INTO_RELEASED | FLS_UNHURRIED)) || (n_in > 0 && (!host_ids || !dev_ids)) || (n_out > 0 && (!out_dev_ids || !out_host_ids))) {
     flp_set_error("fls_submit: invalid argument");
     return FLP_EINVAL;
   }
@@ -170,18 +170,19 @@ extern "C" flp_status fls_submit(fls_sched* s, int64_t req_id, int32_t n_in, con
     // a request that moves blocks both ways has its two kernels share the host link: the fetch, which the
     // request's compute waits for, is launched wider than the write-back
     const bool duplex = n_in > 0 && n_out > 0;
+    const int width = (flags & FLS_UNHURRIED) ? FLP_WIDTH_NARROW : duplex ? FLP_WIDTH_DUPLEX : FLP_WIDTH_SINGLE;
     // fetches land in blocks that an earlier request's write-back may have released
     if (s->have_out) FLP_TRY_HIP(hipStreamWaitEvent(s->s_in, s->ev_out, 0));
     if (n_out > 0) {
       // the compute announced last may still append to the blocks that go out
       if (s->have_compute) FLP_TRY_HIP(hipStreamWaitEvent(s->s_out, s->ev_compute, 0));
-      FLP_TRY(flp_swap_duplex(s->pool, n_out, out_dev_ids, out_host_ids, 0, s->s_out, duplex));
+      FLP_TRY(flp_swap_duplex(s->pool, n_out, out_dev_ids, out_host_ids, 0, s->s_out, width));
       FLP_TRY_HIP(hipEventRecord(s->ev_out, s->s_out));
       s->have_out = true;
       // ... or this request's own, when the caller says that they make the room
       if (flags & FLS_FETCH_INTO_RELEASED) FLP_TRY_HIP(hipStreamWaitEvent(s->s_in, s->ev_out, 0));
     }
-    if (n_in > 0) FLP_TRY(flp_swap_duplex(s->pool, n_in, host_ids, dev_ids, 1, s->s_in, duplex));
+    if (n_in > 0) FLP_TRY(flp_swap_duplex(s->pool, n_in, host_ids, dev_ids, 1, s->s_in, width));
     FLP_TRY(take_event(s, &r.done));
     FLP_TRY_HIP(hipEventRecord(r.done, s->s_in));
   }

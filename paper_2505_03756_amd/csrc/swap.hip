@@ -88,8 +88,15 @@ flp_status flp_launch_copy_blocks(const uint8_t* src_base, uint8_t* dst_base, co
   // with both lists) asks for three workgroups per XCD in and one out: 46 and 45 GB/s (a step of 1.44 GB
   // each way: 36.7 ms at 16 and 16, 33.7 ms at 24 and 8; widths that do not divide by the 8 XCDs load
   // them unevenly and do worse).  A tier that lives in device memory wants the whole chip.
-  const int64_t max_wgs = host_link == FLP_LINK_NONE ? 2048 : host_link == FLP_LINK_IN_DUPLEX ? 24
-                          : host_link == FLP_LINK_OUT_DUPLEX ? 8 : 16;
+  // Moves that need not hurry (a small request beside a whole compute step) run on 12 and 4 workgroups: about two
+  // thirds of the rate, and the matrix-bound attention kernel beside them is not slowed at all (12.7 -> 13.0 ms
+  // instead of -> 17.9 ms beside the wide pair).
+  const int64_t max_wgs = host_link == FLP_LINK_NONE         ? 2048
+                          : host_link == FLP_LINK_IN_DUPLEX  ? 24
+                          : host_link == FLP_LINK_OUT_DUPLEX ? 8
+                          : host_link == FLP_LINK_IN_NARROW  ? 12
+                          : host_link == FLP_LINK_OUT_NARROW ? 4
+                                                             : 16;
   dim3 grid((unsigned)(total < max_wgs ? total : max_wgs));
   if (block_bytes % 16 == 0) {
     hipLaunchKernelGGL(copy_blocks_kernel<u32x4>, grid, dim3(kThreads), 0, stream, src_base, dst_base, src_ids_dev,

@@ -50,7 +50,8 @@ class Planner:
 
     __del__ = close
 
-    def submit(self, req_id, host_ids=(), dev_ids=(), out_dev_ids=(), out_host_ids=(), fetch_into_released=False):
+    def submit(self, req_id, host_ids=(), dev_ids=(), out_dev_ids=(), out_host_ids=(), fetch_into_released=False,
+               unhurried=False):
         h, hp = _ids(host_ids)
         d, dp = _ids(dev_ids)
         od, odp = _ids(out_dev_ids)
@@ -58,7 +59,7 @@ class Planner:
         if len(h) != len(d) or len(od) != len(oh):
             raise flpool.FlpError(flpool.FLP_EINVAL, "id lists of one direction must have equal lengths")
         flpool._check(self._lib.fls_submit(self._h, int(req_id), len(h), hp, dp, len(od), odp, ohp,
-                                           1 if fetch_into_released else 0))
+                                           (1 if fetch_into_released else 0) | (2 if unhurried else 0)))
 
     def poll(self, max_ready=1 << 20):
         out = np.zeros(max(1, min(max_ready, 1 << 20)), dtype=np.int64)
