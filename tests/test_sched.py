@@ -63,6 +63,11 @@ def test_argument_checks():
     assert e.value.code == flpool.FLP_EINVAL
     with pytest.raises(flpool.FlpError):
         p.submit(2, host_ids=[0, 1], dev_ids=[0])    # lists of one direction differ in length
+    p.submit(3, host_ids=[1], dev_ids=[1], fetch_into_released=True, unhurried=True)   # both flags are known
+    import ctypes as C
+    one = (C.c_int32 * 1)(2)
+    rc = p._lib.fls_submit(p._h, 4, 1, one, one, 0, None, None, 4)                    # an unknown flag is not
+    assert rc == flpool.FLP_EINVAL and p.stats()["submitted"] == 2
     p.close()
     with pytest.raises(flpool.FlpError) as e:
         flsched.Planner(pool=None, manual=False)     # a planner that issues moves needs a pool
