@@ -492,14 +492,18 @@ def run_workload(name, args, headline):
     b.run(args.warmup, timed=False)
     torch.cuda.synchronize()
     gc.collect()
+    clock = ClockSampler(pause=0.05) if headline else None     # what the chip clocks at under the timed steps
     gc.disable()                    # the interpreter's cycle collector costs tens of ms when it strikes inside a step
     try:
+        t_wall0 = time.time()
         wall0 = time.perf_counter()
         recs = b.run(args.steps, timed=True)
         torch.cuda.synchronize()
         wall = time.perf_counter() - wall0
+        t_wall1 = time.time()
     finally:
         gc.enable()
+    sclk = [c for t, c in clock.stop() if t_wall0 + 0.1 <= t <= t_wall1] if clock else []
     tokens = sum(r["st"].n_tokens for r in recs)
     ms_per_step = wall * 1e3 / args.steps
     T_last = recs[-1]["st"].n_tokens
@@ -579,6 +583,9 @@ def run_workload(name, args, headline):
     # the same kernel with nothing beside it (serialised pass, last batch), for the reader of `frac`: in a step that the
     # host link bounds the launches of the timed region run beside both move kernels and are stretched by them
     ka = kernels["attention"]
+    if sclk:
+        roof["sclk_MHz_during_timed_steps"] = {"median": float(np.median(sclk)), "min": int(min(sclk)),
+                                               "max": int(max(sclk)), "samples": len(sclk), "source": "rocm-smi"}
     roof["alone_ms_last_batch"] = ka["ms"]
     roof["frac_alone_last_batch"] = round((ka["TFLOPps"] / MFMA_PEAK_TFLOPS) if roof["bound"] == "mfma"
                                           else (ka["GBps"] / HBM_PEAK_GBS), 4)
@@ -707,13 +714,40 @@ def achievable_rates(stream):
                     "runtime's copy routines, median of 5"}
 
 
+class ClockSampler:
+    """Shader clock as `rocm-smi --showclocks --csv` reports it, sampled by a thread until stop(); samples are
+    (time.time(), MHz).  Any failure of the tool just leaves the list short."""
+
+    def __init__(self, pause=0.25):
+        import threading
+        self.samples, self._stop, self._pause = [], threading.Event(), pause
+        self._th = threading.Thread(target=self._run, daemon=True)
+        self._th.start()
+
+    def _run(self):
+        import re
+        import subprocess
+        while not self._stop.is_set():
+            try:
+                r = subprocess.run(["/opt/rocm/bin/rocm-smi", "--showclocks", "--csv"], capture_output=True, text=True,
+                                   timeout=10)
+                m = re.findall(r"\((\d+)Mhz\)", r.stdout.strip().splitlines()[-1])
+                if m:
+                    self.samples.append((time.time(), int(m[-1])))     # the last clock of the row is sclk
+            except (OSError, subprocess.SubprocessError, IndexError):
+                pass
+            self._stop.wait(self._pause)
+
+    def stop(self):
+        self._stop.set()
+        self._th.join(timeout=15)
+        return self.samples
+
+
 def attention_clock(args):
     """The attention stage alone, back to back for some seconds, with the shader clock sampled from rocm-smi beside
     it: on the pool as drawn (N(0,1) keys and values) and on a zeroed pool.  The instruction stream is the same in
     both phases; what differs is the power the matrix cores draw, and with it the clock the chip holds."""
-    import re
-    import subprocess
-    import threading
     import numpy as np
     import torch
     name = args.workload or WORKLOADS[0]
@@ -723,22 +757,8 @@ def attention_clock(args):
     torch.cuda.synchronize()
     st = recs[-1]["st"]
     flops = b.work(st)["attn_flops"]
-    samples, stop = [], threading.Event()
-
-    def sampler():
-        while not stop.is_set():
-            try:
-                r = subprocess.run(["/opt/rocm/bin/rocm-smi", "--showclocks", "--csv"], capture_output=True, text=True,
-                                   timeout=10)
-                m = re.findall(r"\((\d+)Mhz\)", r.stdout.strip().splitlines()[-1])
-                if m:
-                    samples.append((time.time(), int(m[-1])))      # the last clock of the row is sclk
-            except (OSError, subprocess.SubprocessError, IndexError):
-                pass
-            time.sleep(0.25)
-
-    th = threading.Thread(target=sampler)
-    th.start()
+    clock = ClockSampler()
+    samples = clock.samples
     out = {"workload": name, "tokens": st.n_tokens, "flops_per_launch": flops, "phases": []}
     try:
         for phase in ("pool as drawn", "pool zeroed"):
@@ -764,8 +784,7 @@ def attention_clock(args):
                                   "sclk_MHz_min_max": [min(clk), max(clk)] if clk else None, "sclk_samples": len(clk)})
             time.sleep(1.5)
     finally:
-        stop.set()
-        th.join()
+        clock.stop()
     idle = [c for t, c in samples[-4:]]
     out["sclk_MHz_idle_after"] = idle
     print(json.dumps(out))
