@@ -103,7 +103,7 @@ enum { FLP_LINK_NONE = 0, FLP_LINK_IN = 1, FLP_LINK_OUT = 2, FLP_LINK_IN_DUPLEX 
 // flp_pool_swap_in / flp_pool_swap_out (src_tier 1 / 0) for a caller that knows what runs beside the move: one
 // direction alone, both directions together, or moves that need not hurry
 enum { FLP_WIDTH_SINGLE = 0, FLP_WIDTH_DUPLEX = 1, FLP_WIDTH_NARROW = 2 };
-flp_status flp_swap_duplex(flp_pool* p, int32_t n, const int32_t* src_ids, const int32_t* dst_ids, int src_tier,
+flp_status flp_swap_width(flp_pool* p, int32_t n, const int32_t* src_ids, const int32_t* dst_ids, int src_tier,
                            void* hip_stream, int width);
 
 flp_status flp_launch_stage_copy(const void* src_pinned, void* dst_dev, size_t bytes, hipStream_t stream);

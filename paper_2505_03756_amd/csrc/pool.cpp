@@ -340,7 +340,7 @@ static flp_status swap_common(flp_pool* p, int32_t n, const int32_t* src_ids, co
   return st != FLP_OK ? st : st2;
 }
 
-flp_status flp_swap_duplex(flp_pool* p, int32_t n, const int32_t* src_ids, const int32_t* dst_ids, int src_tier,
+flp_status flp_swap_width(flp_pool* p, int32_t n, const int32_t* src_ids, const int32_t* dst_ids, int src_tier,
                            void* hip_stream, int width) {
   return swap_common(p, n, src_ids, dst_ids, src_tier, hip_stream, src_tier == 1 ? "fetch" : "write-back", width);
 }

@@ -176,13 +176,13 @@ extern "C" flp_status fls_submit(fls_sched* s, int64_t req_id, int32_t n_in, con
     if (n_out > 0) {
       // the compute announced last may still append to the blocks that go out
       if (s->have_compute) FLP_TRY_HIP(hipStreamWaitEvent(s->s_out, s->ev_compute, 0));
-      FLP_TRY(flp_swap_duplex(s->pool, n_out, out_dev_ids, out_host_ids, 0, s->s_out, width));
+      FLP_TRY(flp_swap_width(s->pool, n_out, out_dev_ids, out_host_ids, 0, s->s_out, width));
       FLP_TRY_HIP(hipEventRecord(s->ev_out, s->s_out));
       s->have_out = true;
       // ... or this request's own, when the caller says that they make the room
       if (flags & FLS_FETCH_INTO_RELEASED) FLP_TRY_HIP(hipStreamWaitEvent(s->s_in, s->ev_out, 0));
     }
-    if (n_in > 0) FLP_TRY(flp_swap_duplex(s->pool, n_in, host_ids, dev_ids, 1, s->s_in, width));
+    if (n_in > 0) FLP_TRY(flp_swap_width(s->pool, n_in, host_ids, dev_ids, 1, s->s_in, width));
     FLP_TRY(take_event(s, &r.done));
     FLP_TRY_HIP(hipEventRecord(r.done, s->s_in));
   }
